@@ -1,0 +1,187 @@
+/*
+ * mc_kv.h -- C ABI of the MI355X (gfx950) paged KV-cache hot path.
+ *
+ * The calls are the data-plane half of the unified KV cache interface of
+ * "A System for Microserving of LLMs" (arXiv 2412.12488), Sec. 3.4:
+ *   - prep_recv allocates KV entries (page index + slot index, Sec. 3.2
+ *     Example 2) for the part of a prompt the engine does not hold
+ *                                                   -> mc_kv_alloc_pages
+ *   - begin_forward plans the metadata once for all attention layers
+ *                                                   -> mc_attn_plan
+ *   - attention(qkv_data) writes the new K/V into the cache and attends the
+ *     new tokens over the cached prefix and themselves (start_generate
+ *     prefills prompt[begin:] over the cached prompt[:begin], Sec. 3.1; the
+ *     balanced split continues with prompt[s:], Sec. 3.3)
+ *                                   -> mc_kv_append, mc_prefix_prefill_attn
+ *   - remote_send moves the KV of prompt[begin:end] into the entries the
+ *     receiver reserved (Sec. 3.1, Sec. 3.5); on one GPU the wire is replaced
+ *     by a contiguous buffer in HBM
+ *                                   -> mc_kv_pack_range, mc_kv_unpack_range
+ *
+ * The paper fixes no dtype, page size, page layout, softmax scale or LSE base;
+ * the choices below are this library's.
+ *
+ * Conventions for every call
+ *   - Plain pointers and sizes only.  "device" = HIP device memory of the
+ *     current device, "host" = ordinary host memory.
+ *   - All device memory is owned by the caller and must stay valid until the
+ *     work queued on `stream` has finished.  The library owns only the host
+ *     allocator object made by mc_kv_allocator_create.
+ *   - Calls that take a `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) only enqueue kernels: they never synchronise, never
+ *     allocate, never copy from host.  Arguments are validated on the host
+ *     before anything is launched; on any error nothing is launched.
+ *   - Values that live in device arrays (page ids, offsets) cannot be seen by
+ *     the host.  Kernels bounds-check every page id against the pool and every
+ *     page-table index against the sequence's table; an entry that fails is
+ *     skipped (no read, no write) and, for attention, reported through
+ *     mc_attn_plan_check.
+ *   - Return value: mc_status (MC_OK = 0).
+ *
+ * Layouts (2-byte elements, fp16 or bf16, head_dim D = 128, page size P = 16)
+ *   pool     [layer][page][2: 0=K 1=V][kv_head][slot][D]
+ *            one (layer,page,K|V,kv_head) block is a contiguous 4 KiB run
+ *   q, out   [token][q_head][D]        tokens of all sequences back to back
+ *   k_new    [token][kv_head][D]       (v_new likewise)
+ *   lse      [token][q_head]  float32, natural log of sum_j exp(scale * q.k_j)
+ *   sendbuf  [layer - layer_begin][2][token - s0][kv_head][D]
+ *   page_table  int32 page ids of all sequences back to back; sequence s owns
+ *            entries [cu_pages[s], cu_pages[s+1]); entry i holds tokens
+ *            [16 i, 16 i + 16) of the sequence
+ *   cu_q     int32 [batch+1], cu_q[s+1]-cu_q[s] = new tokens of sequence s
+ *   begin    int32 [batch], cached prefix length of sequence s; its new tokens
+ *            are positions [begin[s], begin[s] + q_s)
+ * Ranges are token-granular: begin, end, s0, s1 need not be multiples of 16.
+ */
+#ifndef MC_KV_H_
+#define MC_KV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MC_OK = 0,
+  MC_ERR_INVALID = 1,     /* null pointer, negative size, misaligned pointer, bad handle */
+  MC_ERR_NO_PAGES = 2,    /* allocator cannot satisfy the request; nothing was taken */
+  MC_ERR_RANGE = 3,       /* layer / token range / table length outside the pool or table */
+  MC_ERR_ALIAS = 4,       /* a destination page is listed twice */
+  MC_ERR_UNSUPPORTED = 5, /* head_dim != 128, page_size != 16, unknown dtype, GQA ratio */
+  MC_ERR_HIP = 6          /* a HIP launch failed */
+} mc_status;
+
+typedef enum { MC_F16 = 0, MC_BF16 = 1 } mc_dtype;
+
+/* One page pool.  `base` is device memory, 16-byte aligned, of
+ * num_layers*num_pages*2*num_kv_heads*page_size*head_dim 2-byte elements. */
+typedef struct {
+  void* base;
+  int32_t num_layers;
+  int32_t num_pages;
+  int32_t page_size;    /* must be 16 */
+  int32_t num_kv_heads;
+  int32_t head_dim;     /* must be 128 */
+  int32_t dtype;        /* mc_dtype */
+} mc_pool_desc;
+
+/* Human-readable name of a status code (static storage). */
+const char* mc_status_string(int32_t status);
+/* Bumped on any incompatible change of this header. */
+int32_t mc_abi_version(void);
+
+/* ---- page allocator (prep_recv "allocates KV cache entries", Sec. 3.1) ----
+ * Host-only LIFO free list over page ids [0, num_pages).  A fresh allocator
+ * hands out 0, 1, 2, ...; freed pages are pushed in argument order, so the last
+ * page of the last free call is handed out next.  Not thread-safe. */
+mc_status mc_kv_allocator_create(int32_t num_pages, void** alloc_out /* host */);
+mc_status mc_kv_allocator_destroy(void* alloc);
+/* All-or-nothing: MC_ERR_NO_PAGES leaves the allocator unchanged. */
+mc_status mc_kv_alloc_pages(void* alloc, int32_t n, int32_t* pages_out /* host, n entries */);
+/* MC_ERR_INVALID (nothing freed) if a page is out of range, not allocated, or listed twice. */
+mc_status mc_kv_free_pages(void* alloc, int32_t n, const int32_t* pages /* host */);
+mc_status mc_kv_allocator_num_free(void* alloc, int32_t* num_free_out /* host */);
+/* Host check of a destination page table before append / unpack: MC_ERR_RANGE if an
+ * id is outside [0,num_pages), MC_ERR_ALIAS if one appears twice, else MC_OK. */
+mc_status mc_kv_check_page_table(const int32_t* pages /* host */, int64_t n, int32_t num_pages);
+
+/* ---- append: write new K/V into their (page, slot) entries -----------------
+ * (the KV-write half of attention(qkv_data), Sec. 3.4; "new KVs are first
+ * materialized through prefill computation", Sec. 3.1).
+ * Token g of sequence s (cu_q[s] <= g < cu_q[s+1]) has position
+ * pos = begin[s] + g - cu_q[s] and goes to page page_table[cu_pages[s] + pos/16],
+ * slot pos%16, of `layer`.  No other byte of the pool is written.  Two tokens
+ * mapping to one (page, slot) is a caller error (undefined which one lands).
+ * total_q = cu_q[batch] (host copy, sizes the launch); 0 is legal. */
+mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer,
+                       const void* k_new /* device [total_q][Hkv][D] */,
+                       const void* v_new /* device [total_q][Hkv][D] */,
+                       int32_t batch, int32_t total_q,
+                       const int32_t* cu_q /* device [batch+1] */,
+                       const int32_t* begin /* device [batch] */,
+                       const int32_t* page_table /* device */,
+                       const int32_t* cu_pages /* device [batch+1] */,
+                       void* stream);
+
+/* ---- attention of the new range over the paged cache -----------------------
+ * For sequence s, new token at position i in [begin[s], begin[s]+q_s), head h:
+ *   out[i,h,:] = sum_j softmax_j(scale * q[i,h].k[j,h/G]) * v[j,h/G,:],  j in [0, i]
+ *   lse[i,h]   = ln sum_j exp(scale * q[i,h].k[j,h/G])
+ * with G = num_q_heads / num_kv_heads in {1,2,4,8}; K and V of every j,
+ * including the new range, are read from the pages (mc_kv_append of this layer
+ * comes first on the same stream).  Accumulation and softmax are fp32, out is
+ * rounded to the pool dtype.  Page tables of different sequences may share
+ * pages (shared prefixes, Sec. 3.4 fork_sequence).
+ *
+ * mc_attn_plan is the declaration stage (begin_forward, Sec. 3.4): it turns the
+ * ragged batch into a work list in `workspace`, validates the device arrays and
+ * is valid for every layer as long as the arrays it was given are unchanged.
+ * mc_prefix_prefill_attn requires a workspace planned with the same arguments.
+ * mc_attn_workspace_size gives the bytes needed (0 on bad arguments);
+ * workspace must be 16-byte aligned. */
+size_t mc_attn_workspace_size(int32_t batch, int32_t total_q, int32_t num_q_heads,
+                              int32_t num_kv_heads);
+mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
+                       int32_t total_q,
+                       const int32_t* cu_q /* device [batch+1] */,
+                       const int32_t* begin /* device [batch] */,
+                       const int32_t* page_table /* device */,
+                       const int32_t* cu_pages /* device [batch+1] */,
+                       void* workspace /* device */, size_t workspace_bytes, void* stream);
+/* Synchronises `stream` and reports what the plan kernel found: MC_OK, or
+ * MC_ERR_RANGE if an offset array is not monotone, a sequence's table is too
+ * short for begin+q tokens, or a page id is outside the pool (then the work
+ * list is empty and attention writes nothing).  The only call here that blocks. */
+mc_status mc_attn_plan_check(const void* workspace /* device */, void* stream);
+mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer,
+                                 const void* q /* device [total_q][Hq][D] */,
+                                 int32_t num_q_heads, int32_t batch, int32_t total_q,
+                                 const int32_t* cu_q, const int32_t* begin,
+                                 const int32_t* page_table, const int32_t* cu_pages,
+                                 float sm_scale /* 0 -> 1/sqrt(D) */,
+                                 void* out /* device [total_q][Hq][D], pool dtype */,
+                                 float* lse /* device [total_q][Hq] */,
+                                 const void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- transfer payload: pages <-> contiguous buffer -------------------------
+ * (sender and receiver side of remote_send: KV of prompt[begin:end] goes to the
+ * page/slot entries reserved by prep_recv, Sec. 3.1, Sec. 3.2 Example 2; a
+ * layer's KV can go as soon as the layer is done, Sec. 3.5, hence layer-major.)
+ * pages: device int32 table of ONE sequence, n_table_pages entries, must cover
+ * token s1-1 (MC_ERR_RANGE otherwise).  Tokens [s0,s1), layers
+ * [layer_begin, layer_end).  pack reads only those slots and writes only
+ * sendbuf; unpack reads only sendbuf and writes only those slots.
+ * s0 == s1 or layer_begin == layer_end: MC_OK, nothing is launched. */
+mc_status mc_kv_pack_range(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                           const int32_t* pages /* device */, int32_t n_table_pages, int32_t s0,
+                           int32_t s1, void* sendbuf /* device, 16-byte aligned */, void* stream);
+mc_status mc_kv_unpack_range(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                             const int32_t* pages /* device */, int32_t n_table_pages, int32_t s0,
+                             int32_t s1, const void* sendbuf /* device */, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MC_KV_H_ */

@@ -1,0 +1,191 @@
+"""ctypes binding of libmc_kv.so: the same names as include/mc_kv.h, argument
+marshalling only.  Device buffers are torch tensors (or raw integer addresses);
+every step of the path runs in the library's HIP kernels.  There is no fallback:
+if the library is missing or a call fails, this raises."""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmc_kv.so")
+
+MC_OK, MC_ERR_INVALID, MC_ERR_NO_PAGES, MC_ERR_RANGE, MC_ERR_ALIAS, MC_ERR_UNSUPPORTED, \
+    MC_ERR_HIP = range(7)
+MC_F16, MC_BF16 = 0, 1
+
+EXPORTS = [
+    "mc_status_string", "mc_abi_version",
+    "mc_kv_allocator_create", "mc_kv_allocator_destroy", "mc_kv_alloc_pages", "mc_kv_free_pages",
+    "mc_kv_allocator_num_free", "mc_kv_check_page_table",
+    "mc_kv_append", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_check",
+    "mc_prefix_prefill_attn", "mc_kv_pack_range", "mc_kv_unpack_range",
+]
+
+
+class McError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+class mc_pool_desc(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("num_layers", C.c_int32), ("num_pages", C.c_int32),
+                ("page_size", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the built library; build it only if nothing is built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    pd = C.POINTER(mc_pool_desc)
+    L.mc_status_string.argtypes = [i32]
+    L.mc_status_string.restype = C.c_char_p
+    L.mc_abi_version.argtypes = []
+    L.mc_kv_allocator_create.argtypes = [i32, C.POINTER(vp)]
+    L.mc_kv_allocator_destroy.argtypes = [vp]
+    L.mc_kv_alloc_pages.argtypes = [vp, i32, C.POINTER(i32)]
+    L.mc_kv_free_pages.argtypes = [vp, i32, C.POINTER(i32)]
+    L.mc_kv_allocator_num_free.argtypes = [vp, C.POINTER(i32)]
+    L.mc_kv_check_page_table.argtypes = [C.POINTER(i32), i64, i32]
+    L.mc_kv_append.argtypes = [pd, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+    L.mc_attn_workspace_size.argtypes = [i32, i32, i32, i32]
+    L.mc_attn_workspace_size.restype = sz
+    L.mc_attn_plan.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.mc_attn_plan_check.argtypes = [vp, vp]
+    L.mc_prefix_prefill_attn.argtypes = [pd, i32, vp, i32, i32, i32, vp, vp, vp, vp, C.c_float,
+                                         vp, vp, vp, sz, vp]
+    L.mc_kv_pack_range.argtypes = [pd, i32, i32, vp, i32, i32, i32, vp, vp]
+    L.mc_kv_unpack_range.argtypes = [pd, i32, i32, vp, i32, i32, i32, vp, vp]
+    _lib = L
+    return L
+
+
+def _ptr(x):
+    """Device (or host) address of a tensor, an int address, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status: int, where: str):
+    if status != MC_OK:
+        raise McError(status, where)
+
+
+def _i32_array(values):
+    arr = (C.c_int32 * max(len(values), 1))(*[int(v) for v in values])
+    return arr
+
+
+def status_string(status: int) -> str:
+    return lib().mc_status_string(int(status)).decode()
+
+
+mc_status_string = status_string
+
+
+def mc_abi_version() -> int:
+    return lib().mc_abi_version()
+
+
+def pool_desc(base, num_layers, num_pages, num_kv_heads, dtype, page_size=16, head_dim=128):
+    return mc_pool_desc(_ptr(base), num_layers, num_pages, page_size, num_kv_heads, head_dim, dtype)
+
+
+# ---- allocator (host) ---------------------------------------------------------
+def mc_kv_allocator_create(num_pages: int):
+    h = C.c_void_p()
+    _check(lib().mc_kv_allocator_create(num_pages, C.byref(h)), "mc_kv_allocator_create")
+    return h
+
+
+def mc_kv_allocator_destroy(alloc):
+    _check(lib().mc_kv_allocator_destroy(alloc), "mc_kv_allocator_destroy")
+
+
+def mc_kv_alloc_pages(alloc, n: int):
+    out = (C.c_int32 * max(n, 1))()
+    _check(lib().mc_kv_alloc_pages(alloc, n, out), "mc_kv_alloc_pages")
+    return list(out[:n])
+
+
+def mc_kv_free_pages(alloc, pages):
+    _check(lib().mc_kv_free_pages(alloc, len(pages), _i32_array(pages)), "mc_kv_free_pages")
+
+
+def mc_kv_allocator_num_free(alloc) -> int:
+    n = C.c_int32()
+    _check(lib().mc_kv_allocator_num_free(alloc, C.byref(n)), "mc_kv_allocator_num_free")
+    return n.value
+
+
+def mc_kv_check_page_table(pages, num_pages: int) -> int:
+    """Returns the status code (MC_OK / MC_ERR_RANGE / MC_ERR_ALIAS) instead of raising."""
+    return lib().mc_kv_check_page_table(_i32_array(pages), len(pages), num_pages)
+
+
+# ---- device calls -------------------------------------------------------------
+def mc_kv_append(pool: mc_pool_desc, layer, k_new, v_new, batch, total_q, cu_q, begin,
+                 page_table, cu_pages, stream=None):
+    _check(lib().mc_kv_append(C.byref(pool), layer, _ptr(k_new), _ptr(v_new), batch, total_q,
+                              _ptr(cu_q), _ptr(begin), _ptr(page_table), _ptr(cu_pages),
+                              _stream(stream)), "mc_kv_append")
+
+
+def mc_attn_workspace_size(batch, total_q, num_q_heads, num_kv_heads) -> int:
+    return lib().mc_attn_workspace_size(batch, total_q, num_q_heads, num_kv_heads)
+
+
+def mc_attn_plan(pool: mc_pool_desc, num_q_heads, batch, total_q, cu_q, begin, page_table,
+                 cu_pages, workspace, workspace_bytes, stream=None):
+    _check(lib().mc_attn_plan(C.byref(pool), num_q_heads, batch, total_q, _ptr(cu_q), _ptr(begin),
+                              _ptr(page_table), _ptr(cu_pages), _ptr(workspace), workspace_bytes,
+                              _stream(stream)), "mc_attn_plan")
+
+
+def mc_attn_plan_check(workspace, stream=None):
+    _check(lib().mc_attn_plan_check(_ptr(workspace), _stream(stream)), "mc_attn_plan_check")
+
+
+def mc_prefix_prefill_attn(pool: mc_pool_desc, layer, q, num_q_heads, batch, total_q, cu_q, begin,
+                           page_table, cu_pages, sm_scale, out, lse, workspace, workspace_bytes,
+                           stream=None):
+    _check(lib().mc_prefix_prefill_attn(C.byref(pool), layer, _ptr(q), num_q_heads, batch, total_q,
+                                        _ptr(cu_q), _ptr(begin), _ptr(page_table), _ptr(cu_pages),
+                                        float(sm_scale), _ptr(out), _ptr(lse), _ptr(workspace),
+                                        workspace_bytes, _stream(stream)),
+           "mc_prefix_prefill_attn")
+
+
+def mc_kv_pack_range(pool: mc_pool_desc, layer_begin, layer_end, pages, n_table_pages, s0, s1,
+                     sendbuf, stream=None):
+    _check(lib().mc_kv_pack_range(C.byref(pool), layer_begin, layer_end, _ptr(pages),
+                                  n_table_pages, s0, s1, _ptr(sendbuf), _stream(stream)),
+           "mc_kv_pack_range")
+
+
+def mc_kv_unpack_range(pool: mc_pool_desc, layer_begin, layer_end, pages, n_table_pages, s0, s1,
+                       sendbuf, stream=None):
+    _check(lib().mc_kv_unpack_range(C.byref(pool), layer_begin, layer_end, _ptr(pages),
+                                    n_table_pages, s0, s1, _ptr(sendbuf), _stream(stream)),
+           "mc_kv_unpack_range")

@@ -1,0 +1,211 @@
+// Bandwidth-bound page copies for gfx950: KV append, and the page-range
+// gather/scatter behind remote_send / prep_recv (paper Sec. 3.1, Sec. 3.2
+// Example 2, Sec. 3.5).  No arithmetic: every lane moves 16 bytes at a time.
+//
+// Geometry (D = 128, P = 16, 2-byte elements): a (token, head) row is 256 B =
+// 16 lanes x 16 B; a (page, K|V, head) block is 16 rows = 4 KiB contiguous in the
+// pool; in the packed buffer and in k_new/v_new the Hkv rows of one token are
+// contiguous (Hkv x 256 B).  A 256-thread workgroup moves one page of K or V of
+// one layer: per head, its 256 lanes cover the 4 KiB block on the pool side
+// (fully coalesced) and 16 runs of 256 B on the token-major side.
+#include "mc_common.h"
+
+namespace {
+
+using mc::kHeadPageBytes;
+using mc::kPage;
+using mc::kRowBytes;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kMaxHeadsInFlight = 8;  // 16-byte loads a lane keeps in flight
+
+struct RangeArgs {
+  char* pool;             // pool base
+  char* buf;              // packed buffer base
+  const int32_t* pages;   // one sequence's table
+  int64_t layer_stride;   // bytes
+  int64_t page_stride;    // bytes
+  int32_t num_pages;      // pool pages, for the bounds check
+  int32_t n_table_pages;
+  int32_t layer_begin;
+  int32_t s0, s1;
+  int32_t hkv;
+};
+
+// grid.x: page index within [s0/16, ceil(s1/16)); grid.y: (layer - layer_begin)*2 + kv
+template <bool kPack>
+__global__ __launch_bounds__(kThreads) void range_copy_kernel(RangeArgs a) {
+  const int tp = a.s0 / kPage + blockIdx.x;          // table index
+  const int lk = blockIdx.y;
+  const int slot = threadIdx.x >> 4, lane16 = threadIdx.x & 15;
+  const int tok = tp * kPage + slot;
+  if (tp >= a.n_table_pages) return;
+  const int32_t page = a.pages[tp];
+  if (page < 0 || page >= a.num_pages) return;
+  const bool live = tok >= a.s0 && tok < a.s1;
+  const int layer = a.layer_begin + (lk >> 1), kv = lk & 1;
+  const int64_t T = a.s1 - a.s0;
+  char* pool_blk = a.pool + layer * a.layer_stride + page * a.page_stride +
+                   (int64_t)kv * a.hkv * kHeadPageBytes + slot * kRowBytes + lane16 * 16;
+  char* buf_row = a.buf + ((int64_t)lk * T + (tok - a.s0)) * a.hkv * kRowBytes + lane16 * 16;
+  if (!live) return;
+  for (int h0 = 0; h0 < a.hkv; h0 += kMaxHeadsInFlight) {
+    u32x4 r[kMaxHeadsInFlight];
+#pragma unroll
+    for (int i = 0; i < kMaxHeadsInFlight; ++i) {
+      const int h = h0 + i;
+      if (h < a.hkv) {
+        const char* src = kPack ? pool_blk + (int64_t)h * kHeadPageBytes : buf_row + h * kRowBytes;
+        r[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kMaxHeadsInFlight; ++i) {
+      const int h = h0 + i;
+      if (h < a.hkv) {
+        char* dst = kPack ? buf_row + h * kRowBytes : pool_blk + (int64_t)h * kHeadPageBytes;
+        __builtin_nontemporal_store(r[i], reinterpret_cast<u32x4*>(dst));
+      }
+    }
+  }
+}
+
+struct AppendArgs {
+  char* pool_layer;        // pool base + layer offset
+  const char* k_new;
+  const char* v_new;
+  const int32_t* cu_q;
+  const int32_t* begin;
+  const int32_t* page_table;
+  const int32_t* cu_pages;
+  int64_t page_stride;
+  int32_t num_pages;
+  int32_t batch, total_q, hkv;
+};
+
+// grid.x: 16 consecutive tokens of the ragged new-token stream; grid.y: 0 = K, 1 = V
+__global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a) {
+  const int g = blockIdx.x * kPage + (threadIdx.x >> 4);
+  const int lane16 = threadIdx.x & 15;
+  const int kv = blockIdx.y;
+  if (g >= a.total_q) return;
+  // sequence of token g: last s with cu_q[s] <= g
+  int lo = 0, hi = a.batch;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.cu_q[mid] <= g) lo = mid; else hi = mid;
+  }
+  const int s = lo;
+  const int q0 = a.cu_q[s];
+  if (g < q0 || g >= a.cu_q[s + 1]) return;          // malformed offsets: skip
+  const int pos = a.begin[s] + (g - q0);
+  if (pos < 0) return;
+  const int p0 = a.cu_pages[s], p1 = a.cu_pages[s + 1];
+  const int tp = pos / kPage;
+  if (p0 < 0 || tp >= p1 - p0) return;               // table too short: skip
+  const int32_t page = a.page_table[p0 + tp];
+  if (page < 0 || page >= a.num_pages) return;
+  const char* src = (kv ? a.v_new : a.k_new) + (int64_t)g * a.hkv * kRowBytes + lane16 * 16;
+  char* dst = a.pool_layer + page * a.page_stride + (int64_t)kv * a.hkv * kHeadPageBytes +
+              (pos % kPage) * kRowBytes + lane16 * 16;
+  for (int h0 = 0; h0 < a.hkv; h0 += kMaxHeadsInFlight) {
+    u32x4 r[kMaxHeadsInFlight];
+#pragma unroll
+    for (int i = 0; i < kMaxHeadsInFlight; ++i)
+      if (h0 + i < a.hkv)
+        r[i] = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4*>(src + (h0 + i) * kRowBytes));
+#pragma unroll
+    for (int i = 0; i < kMaxHeadsInFlight; ++i)
+      if (h0 + i < a.hkv)
+        __builtin_nontemporal_store(
+            r[i], reinterpret_cast<u32x4*>(dst + (int64_t)(h0 + i) * kHeadPageBytes));
+  }
+}
+
+mc_status range_copy(bool pack, const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                     const int32_t* pages, int32_t n_table_pages, int32_t s0, int32_t s1,
+                     void* sendbuf, void* stream) {
+  mc_status st = mc::check_pool(pool);
+  if (st != MC_OK) return st;
+  if (layer_begin < 0 || layer_end < layer_begin || layer_end > pool->num_layers)
+    return MC_ERR_RANGE;
+  if (s0 < 0 || s1 < s0 || n_table_pages < 0) return MC_ERR_RANGE;
+  if (s0 == s1 || layer_begin == layer_end) return MC_OK;
+  if (!pages || !sendbuf || !mc::aligned16(sendbuf)) return MC_ERR_INVALID;
+  const int64_t need = ((int64_t)s1 + kPage - 1) / kPage;
+  if (need > n_table_pages) return MC_ERR_RANGE;
+  const int64_t gy = 2ll * (layer_end - layer_begin);
+  if (gy > 65535) return MC_ERR_UNSUPPORTED;
+  RangeArgs a;
+  a.pool = static_cast<char*>(pool->base);
+  a.buf = static_cast<char*>(sendbuf);
+  a.pages = pages;
+  a.layer_stride = mc::layer_stride_bytes(pool);
+  a.page_stride = mc::page_stride_bytes(pool);
+  a.num_pages = pool->num_pages;
+  a.n_table_pages = n_table_pages;
+  a.layer_begin = layer_begin;
+  a.s0 = s0;
+  a.s1 = s1;
+  a.hkv = pool->num_kv_heads;
+  const int first = s0 / kPage, last = (s1 - 1) / kPage;
+  dim3 grid(last - first + 1, (unsigned)gy);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (pack)
+    hipLaunchKernelGGL(range_copy_kernel<true>, grid, dim3(kThreads), 0, hs, a);
+  else
+    hipLaunchKernelGGL(range_copy_kernel<false>, grid, dim3(kThreads), 0, hs, a);
+  return mc::launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+mc_status mc_kv_pack_range(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                           const int32_t* pages, int32_t n_table_pages, int32_t s0, int32_t s1,
+                           void* sendbuf, void* stream) {
+  return range_copy(true, pool, layer_begin, layer_end, pages, n_table_pages, s0, s1, sendbuf,
+                    stream);
+}
+
+mc_status mc_kv_unpack_range(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                             const int32_t* pages, int32_t n_table_pages, int32_t s0, int32_t s1,
+                             const void* sendbuf, void* stream) {
+  return range_copy(false, pool, layer_begin, layer_end, pages, n_table_pages, s0, s1,
+                    const_cast<void*>(sendbuf), stream);
+}
+
+mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer, const void* k_new,
+                       const void* v_new, int32_t batch, int32_t total_q, const int32_t* cu_q,
+                       const int32_t* begin, const int32_t* page_table, const int32_t* cu_pages,
+                       void* stream) {
+  mc_status st = mc::check_pool(pool);
+  if (st != MC_OK) return st;
+  if (layer < 0 || layer >= pool->num_layers) return MC_ERR_RANGE;
+  if (batch < 0 || total_q < 0) return MC_ERR_INVALID;
+  if (batch == 0 || total_q == 0) return MC_OK;
+  if (!k_new || !v_new || !cu_q || !begin || !page_table || !cu_pages) return MC_ERR_INVALID;
+  if (!mc::aligned16(k_new) || !mc::aligned16(v_new)) return MC_ERR_INVALID;
+  AppendArgs a;
+  a.pool_layer = static_cast<char*>(pool->base) + layer * mc::layer_stride_bytes(pool);
+  a.k_new = static_cast<const char*>(k_new);
+  a.v_new = static_cast<const char*>(v_new);
+  a.cu_q = cu_q;
+  a.begin = begin;
+  a.page_table = page_table;
+  a.cu_pages = cu_pages;
+  a.page_stride = mc::page_stride_bytes(pool);
+  a.num_pages = pool->num_pages;
+  a.batch = batch;
+  a.total_q = total_q;
+  a.hkv = pool->num_kv_heads;
+  dim3 grid((total_q + kPage - 1) / kPage, 2);
+  hipLaunchKernelGGL(append_kernel, grid, dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  return mc::launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,106 @@
+// Host-only parts of the library: status names, the page allocator behind
+// prep_recv (paper Sec. 3.1: "allocates KV cache entries for the missing
+// subsequence"), and a host check of destination page tables.
+#include <new>
+#include <vector>
+
+#include "mc_common.h"
+
+namespace {
+
+struct Allocator {
+  int32_t num_pages;
+  std::vector<int32_t> free_stack;  // back() is handed out next
+  std::vector<uint8_t> state;       // 0 free, 1 handed out, 2 = seen earlier in this free call
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* mc_status_string(int32_t status) {
+  switch (status) {
+    case MC_OK: return "MC_OK";
+    case MC_ERR_INVALID: return "MC_ERR_INVALID";
+    case MC_ERR_NO_PAGES: return "MC_ERR_NO_PAGES";
+    case MC_ERR_RANGE: return "MC_ERR_RANGE";
+    case MC_ERR_ALIAS: return "MC_ERR_ALIAS";
+    case MC_ERR_UNSUPPORTED: return "MC_ERR_UNSUPPORTED";
+    case MC_ERR_HIP: return "MC_ERR_HIP";
+    default: return "MC_ERR_UNKNOWN";
+  }
+}
+
+int32_t mc_abi_version(void) { return 1; }
+
+mc_status mc_kv_allocator_create(int32_t num_pages, void** alloc_out) {
+  if (!alloc_out || num_pages < 0) return MC_ERR_INVALID;
+  Allocator* a = new (std::nothrow) Allocator();
+  if (!a) return MC_ERR_INVALID;
+  a->num_pages = num_pages;
+  a->free_stack.resize(num_pages);
+  for (int32_t i = 0; i < num_pages; ++i) a->free_stack[i] = num_pages - 1 - i;
+  a->state.assign(num_pages, 0);
+  *alloc_out = a;
+  return MC_OK;
+}
+
+mc_status mc_kv_allocator_destroy(void* alloc) {
+  if (!alloc) return MC_ERR_INVALID;
+  delete static_cast<Allocator*>(alloc);
+  return MC_OK;
+}
+
+mc_status mc_kv_alloc_pages(void* alloc, int32_t n, int32_t* pages_out) {
+  Allocator* a = static_cast<Allocator*>(alloc);
+  if (!a || n < 0 || (n > 0 && !pages_out)) return MC_ERR_INVALID;
+  if (static_cast<size_t>(n) > a->free_stack.size()) return MC_ERR_NO_PAGES;
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t p = a->free_stack.back();
+    a->free_stack.pop_back();
+    a->state[p] = 1;
+    pages_out[i] = p;
+  }
+  return MC_OK;
+}
+
+mc_status mc_kv_free_pages(void* alloc, int32_t n, const int32_t* pages) {
+  Allocator* a = static_cast<Allocator*>(alloc);
+  if (!a || n < 0 || (n > 0 && !pages)) return MC_ERR_INVALID;
+  int32_t seen = 0;
+  bool bad = false;
+  for (; seen < n; ++seen) {
+    int32_t p = pages[seen];
+    if (p < 0 || p >= a->num_pages || a->state[p] != 1) { bad = true; break; }
+    a->state[p] = 2;
+  }
+  if (bad) {
+    for (int32_t i = 0; i < seen; ++i) a->state[pages[i]] = 1;
+    return MC_ERR_INVALID;
+  }
+  for (int32_t i = 0; i < n; ++i) {
+    a->state[pages[i]] = 0;
+    a->free_stack.push_back(pages[i]);
+  }
+  return MC_OK;
+}
+
+mc_status mc_kv_allocator_num_free(void* alloc, int32_t* num_free_out) {
+  Allocator* a = static_cast<Allocator*>(alloc);
+  if (!a || !num_free_out) return MC_ERR_INVALID;
+  *num_free_out = static_cast<int32_t>(a->free_stack.size());
+  return MC_OK;
+}
+
+mc_status mc_kv_check_page_table(const int32_t* pages, int64_t n, int32_t num_pages) {
+  if (n < 0 || num_pages < 0 || (n > 0 && !pages)) return MC_ERR_INVALID;
+  std::vector<uint8_t> seen(static_cast<size_t>(num_pages), 0);
+  for (int64_t i = 0; i < n; ++i) {
+    if (pages[i] < 0 || pages[i] >= num_pages) return MC_ERR_RANGE;
+    if (seen[pages[i]]) return MC_ERR_ALIAS;
+    seen[pages[i]] = 1;
+  }
+  return MC_OK;
+}
+
+}  // extern "C"

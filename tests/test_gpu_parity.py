@@ -1,0 +1,248 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on
+the same seeded inputs.  Bars: bit-exact for every byte the copies touch or must not
+touch; max abs error <= 2e-2 on fp16/bf16 attention outputs; LSE within 1e-3."""
+import numpy as np
+import pytest
+import torch
+
+import mc_inputs as mi
+import oracle
+import paper_2412_12488_amd as mc
+from gpu_harness import (DEV, DevBatch, DevPool, bits, dev, fill_both, gpu_append, gpu_attention,
+                         oracle_rows)
+
+pytestmark = pytest.mark.gpu
+O_TOL, LSE_TOL = 2e-2, 1e-3
+
+
+def small_workload(seed, dtype, Hq, Hkv, lens, begins, num_pages=None, layers=1):
+    n, b = np.array(lens), np.array(begins)
+    need = int(sum(-(-int(t) // 16) for t in n))
+    num_pages = num_pages or need + 7
+    w = mi.Workload(f"small-{seed}", seed, dtype, layers, Hq, Hkv, num_pages, n, b)
+    w.page_tables = mi.scatter_page_tables(mi.rng_for(seed, mi.KIND_TABLE), num_pages, n)
+    return w
+
+
+def canary(seed, elems):
+    return mi.rng_for(seed, 99).integers(0, 65536, size=elems, dtype=np.uint16)
+
+
+# ------------------------------------------------------------------ append ----
+@pytest.mark.parametrize("case", [
+    dict(dtype=mi.F16, Hkv=8, lens=[512], begins=[256]),
+    dict(dtype=mi.BF16, Hkv=8, lens=[45, 1, 300, 16, 77], begins=[13, 0, 299, 16, 0]),
+    dict(dtype=mi.BF16, Hkv=2, lens=[100, 64], begins=[33, 48]),
+    dict(dtype=mi.BF16, Hkv=12, lens=[70], begins=[5]),
+])
+def test_append_bytes(case):
+    w = small_workload(101, case["dtype"], case["Hkv"], case["Hkv"], case["lens"], case["begins"],
+                       layers=2)
+    init = canary(1, DevPool(w).elems)
+    pool = DevPool(w, fill=init)
+    opool = init.copy()
+    db = DevBatch(w)
+    ks, vs = [], []
+    for s in range(w.batch):
+        k, v = w.kv(s, 1)
+        k, v = k[w.b[s]:], v[w.b[s]:]
+        ks.append(k), vs.append(v)
+        if len(k):
+            oracle.append(opool, pool.shape, 1, k, v, int(w.b[s]), w.page_tables[s])
+    gpu_append(pool, 1, dev(np.concatenate(ks)), dev(np.concatenate(vs)), db)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(pool.t), opool)          # addressed slots and every other byte
+    assert not np.array_equal(opool, init)
+
+
+def test_append_nothing_is_a_no_op():
+    w = small_workload(102, mi.BF16, 8, 8, [32], [32])
+    init = canary(2, DevPool(w).elems)
+    pool = DevPool(w, fill=init)
+    db = DevBatch(w)
+    gpu_append(pool, 0, dev(np.zeros(16, np.uint16)), dev(np.zeros(16, np.uint16)), db)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(pool.t), init)
+
+
+# ------------------------------------------------------------- pack / unpack ----
+@pytest.mark.parametrize("s0,s1", [(0, 256), (0, 512), (13, 40), (7, 8), (16, 48), (250, 507),
+                                   (511, 512), (100, 100)])
+@pytest.mark.parametrize("Hkv", [8, 3])
+def test_pack_unpack_bytes(s0, s1, Hkv):
+    L = 3
+    w = small_workload(103, mi.F16, Hkv, Hkv, [512], [0], num_pages=64, layers=L)
+    init = canary(3, DevPool(w).elems)
+    pool_a = DevPool(w, fill=init)
+    table = w.page_tables[0]
+    T = s1 - s0
+    guard = 64
+    payload = (L - 1) * 2 * T * Hkv * 128
+    raw = canary(4, payload + 2 * guard)
+    send = dev(raw)
+    mc.mc_kv_pack_range(pool_a.desc, 1, L, dev(table), len(table), s0, s1, send[guard:])
+    torch.cuda.synchronize()
+    got = bits(send)
+    ref = oracle.pack(init, pool_a.shape, 1, L, table, s0, s1)
+    assert np.array_equal(got[guard:guard + payload], ref.ravel())
+    assert np.array_equal(got[:guard], raw[:guard]) and np.array_equal(got[guard + payload:],
+                                                                      raw[guard + payload:])
+    assert np.array_equal(bits(pool_a.t), init)                      # pack writes no page
+    # receiver: a second pool with its own table and canaries
+    init_b = canary(5, pool_a.elems)
+    pool_b = DevPool(w, fill=init_b)
+    table_b = mi.rng_for(6).permutation(64)[: len(table)].astype(np.int32)
+    mc.mc_kv_unpack_range(pool_b.desc, 1, L, dev(table_b), len(table_b), s0, s1, send[guard:])
+    torch.cuda.synchronize()
+    opool_b = init_b.copy()
+    oracle.unpack(opool_b, pool_a.shape, 1, L, table_b, s0, s1, ref)
+    assert np.array_equal(bits(pool_b.t), opool_b)
+
+
+def test_transfer_then_attend_equals_local_attention():
+    """KV sent to a second pool is attended there exactly as at home (Sec. 3.4)."""
+    w = small_workload(104, mi.BF16, 32, 8, [200], [150], num_pages=40)
+    pool_a, opool = DevPool(w), None
+    opool = oracle.new_pool(pool_a.shape)
+    fill_both(w, pool_a, opool)
+    table = w.page_tables[0]
+    send = torch.zeros(2 * 200 * 8 * 128, dtype=torch.int16, device=DEV)
+    mc.mc_kv_pack_range(pool_a.desc, 0, 1, dev(table), len(table), 0, 200, send)
+    pool_b = DevPool(w)
+    table_b = mi.rng_for(7).permutation(40)[: len(table)].astype(np.int32)
+    mc.mc_kv_unpack_range(pool_b.desc, 0, 1, dev(table_b), len(table_b), 0, 200, send)
+    wb = mi.Workload("b", w.seed, w.dtype, 1, 32, 8, 40, w.n, w.b, [table_b])
+    q = w.q(0)
+    oa, la = gpu_attention(pool_a, 0, dev(q), DevBatch(w))
+    ob, lb = gpu_attention(pool_b, 0, dev(q), DevBatch(wb))
+    assert torch.equal(oa, ob) and torch.equal(la, lb)
+
+
+# ---------------------------------------------------------------- attention ----
+def check_attention(w, layer=0, scale=None, sample=None, seed=0):
+    pool = DevPool(w)
+    opool = oracle.new_pool(pool.shape)
+    fill_both(w, pool, opool, layers=(layer,))
+    db = DevBatch(w)
+    qs = [w.q(s, layer) for s in range(w.batch)]
+    out, lse = gpu_attention(pool, layer, dev(np.concatenate(qs)), db,
+                             sm_scale=0.0 if scale is None else scale)
+    out_b, lse_h = bits(out), lse.cpu().numpy().astype(np.float64)
+    worst_o = worst_l = 0.0
+    for s in range(w.batch):
+        q_len = int(w.n[s] - w.b[s])
+        if q_len == 0:
+            continue
+        lo = int(w.cu_q[s])
+        go = oracle.decode(out_b[lo:lo + q_len], w.dtype)
+        gl = lse_h[lo:lo + q_len]
+        if sample is None:
+            ro, rl = oracle_rows(w, opool, pool.shape, layer, s, qs[s], scale=scale)
+        else:
+            rows, heads = mi.sample_rows(mi.rng_for(seed, s, 5), q_len, int(w.b[s]),
+                                         w.num_q_heads, sample)
+            ro, rl = oracle_rows(w, opool, pool.shape, layer, s, qs[s], rows, heads, scale=scale)
+            go, gl = go[rows, heads], gl[rows, heads]
+        assert np.all(np.isfinite(go)) and np.all(np.isfinite(gl))
+        worst_o = max(worst_o, float(np.max(np.abs(go - ro))))
+        worst_l = max(worst_l, float(np.max(np.abs(gl - rl))))
+    assert worst_o <= O_TOL, worst_o
+    assert worst_l <= LSE_TOL, worst_l
+    return worst_o, worst_l
+
+
+@pytest.mark.parametrize("dtype", [mi.F16, mi.BF16])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (4, 2), (32, 8), (16, 2)])
+def test_attention_small_all_rows(dtype, Hq, Hkv):
+    # several q tiles and KV tiles, ragged tails, unaligned prefixes, one-token and
+    # no-prefix sequences, and a sequence with nothing new
+    lens = [333, 64, 130, 1, 257, 90]
+    begins = [77, 0, 129, 0, 256, 90]
+    w = small_workload(200 + Hq, dtype, Hq, Hkv, lens, begins)
+    check_attention(w)
+
+
+def test_attention_custom_scale_and_layer():
+    w = small_workload(210, mi.BF16, 32, 8, [150, 40], [31, 8], layers=3)
+    check_attention(w, layer=2, scale=0.05)
+
+
+def test_attention_writes_only_its_rows():
+    w = small_workload(211, mi.BF16, 32, 8, [100, 0 + 50], [40, 50])   # second sequence: nothing new
+    pool = DevPool(w)
+    opool = oracle.new_pool(pool.shape)
+    fill_both(w, pool, opool)
+    db = DevBatch(w)
+    out, lse = gpu_attention(pool, 0, dev(w.q(0)), db)
+    assert out.shape[0] == 60 and torch.isfinite(lse).all()
+
+
+def test_plan_reports_bad_tables():
+    w = small_workload(212, mi.BF16, 32, 8, [100], [40])
+    pool = DevPool(w)
+    db = DevBatch(w)
+    ws_bytes = mc.mc_attn_workspace_size(1, 60, 32, 8)
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=DEV)
+    bad = db.page_table.clone()
+    bad[3] = w.num_pages            # page id outside the pool
+    mc.mc_attn_plan(pool.desc, 32, 1, 60, db.cu_q, db.begin, bad, db.cu_pages, ws, ws_bytes)
+    with pytest.raises(mc.McError) as e:
+        mc.mc_attn_plan_check(ws)
+    assert e.value.status == mc.MC_ERR_RANGE
+    short = dev(np.array([0, 3], dtype=np.int32))   # 3 pages cannot hold 100 tokens
+    mc.mc_attn_plan(pool.desc, 32, 1, 60, db.cu_q, db.begin, db.page_table, short, ws, ws_bytes)
+    with pytest.raises(mc.McError):
+        mc.mc_attn_plan_check(ws)
+    # attention over the failed plan launches but writes nothing
+    out = torch.full((60, 32, 128), 0x7fc1, dtype=torch.int16, device=DEV)
+    lse = torch.full((60, 32), -7.0, dtype=torch.float32, device=DEV)
+    mc.mc_prefix_prefill_attn(pool.desc, 0, dev(w.q(0)), 32, 1, 60, db.cu_q, db.begin,
+                              db.page_table, short, 0.0, out, lse, ws, ws_bytes)
+    torch.cuda.synchronize()
+    assert (lse == -7.0).all() and (out == 0x7fc1).all()
+
+
+def test_split_range_equals_single_pass_on_gpu():
+    """Pass A over [0,m) then pass B over [m,n) against the cached [0,m) reproduces the
+    single [0,n) pass row for row (Sec. 3.3)."""
+    n = [300, 170]
+    m = [150, 85]
+    w_full = small_workload(213, mi.BF16, 32, 8, n, [0, 0])
+    pool = DevPool(w_full)
+    opool = oracle.new_pool(pool.shape)
+    fill_both(w_full, pool, opool)
+    q_full = [w_full.q(s) for s in range(2)]
+    o_full, l_full = gpu_attention(pool, 0, dev(np.concatenate(q_full)), DevBatch(w_full))
+    w_a = w_full.with_ranges([0, 0], m)
+    w_b = w_full.with_ranges(m, n)
+    o_a, l_a = gpu_attention(pool, 0, dev(np.concatenate([q_full[s][: m[s]] for s in range(2)])),
+                             DevBatch(w_a))
+    o_b, l_b = gpu_attention(pool, 0, dev(np.concatenate([q_full[s][m[s]:] for s in range(2)])),
+                             DevBatch(w_b))
+    f = lambda t: oracle.decode(bits(t), mi.BF16)
+    full, la_full = f(o_full), l_full.cpu().numpy()
+    parts = np.concatenate([f(o_a)[:150], f(o_b)[:150], f(o_a)[150:], f(o_b)[150:]])
+    lparts = np.concatenate([l_a.cpu().numpy()[:150], l_b.cpu().numpy()[:150],
+                             l_a.cpu().numpy()[150:], l_b.cpu().numpy()[150:]])
+    # different tilings of the same rows: equal within the tolerance, not bit-wise
+    assert np.max(np.abs(parts - full)) <= O_TOL
+    assert np.max(np.abs(lparts - la_full)) <= LSE_TOL
+
+
+# ------------------------------------------------------- the five configs ----
+def test_config1_full():
+    w = mi.config(1)
+    check_attention(w)
+
+
+def test_config2_sampled():
+    check_attention(mi.config(2), sample=512, seed=2)
+
+
+def test_config4_sampled():
+    check_attention(mi.config(4), sample=512, seed=4)
+
+
+def test_paper_shaped_points():
+    for cached in (500, 2500, 4500):
+        check_attention(mi.paper_point(cached), sample=256, seed=cached)

@@ -1,0 +1,155 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header
+declares, its host allocator agrees with the oracle's, and argument validation
+rejects bad calls before anything would be launched (no compute call is made here)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import mc_inputs as mi
+import oracle
+import paper_2412_12488_amd as mc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a non-null, 16-byte aligned "device address" that is never dereferenced
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "mc_kv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_symbols()
+    assert "mc_prefix_prefill_attn" in names and "mc_kv_pack_range" in names
+    L = mc.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(mc.EXPORTS) == names
+    assert mc.mc_abi_version() == 1
+    assert mc.status_string(0) == "MC_OK" and mc.status_string(3) == "MC_ERR_RANGE"
+
+
+def test_allocator_matches_oracle_on_random_traffic():
+    rng = mi.rng_for(60)
+    for num_pages in (0, 1, 4, 64, 1000):
+        a = mc.mc_kv_allocator_create(num_pages)
+        o = oracle.Allocator(num_pages)
+        held = []
+        for _ in range(300):
+            if rng.random() < 0.55 or not held:
+                n = int(rng.integers(0, max(2, num_pages // 3 + 2)))
+                ref = o.take(n)
+                if ref is None:
+                    with pytest.raises(mc.McError) as e:
+                        mc.mc_kv_alloc_pages(a, n)
+                    assert e.value.status == mc.MC_ERR_NO_PAGES
+                else:
+                    assert mc.mc_kv_alloc_pages(a, n) == ref
+                    held += ref
+            else:
+                k = int(rng.integers(1, len(held) + 1))
+                idx = rng.permutation(len(held))[:k]
+                pages = [held[i] for i in idx]
+                assert o.give(pages)
+                mc.mc_kv_free_pages(a, pages)
+                held = [p for i, p in enumerate(held) if i not in set(idx.tolist())]
+            assert mc.mc_kv_allocator_num_free(a) == o.num_free
+        # double free / foreign page / duplicate are rejected and change nothing
+        free_before = mc.mc_kv_allocator_num_free(a)
+        for bad in ([num_pages], [-1], held[:1] * 2 if held else [0, 0]):
+            with pytest.raises(mc.McError) as e:
+                mc.mc_kv_free_pages(a, bad)
+            assert e.value.status == mc.MC_ERR_INVALID
+            assert not o.give(bad)
+        assert mc.mc_kv_allocator_num_free(a) == free_before
+        mc.mc_kv_allocator_destroy(a)
+
+
+def test_first_allocations_are_0_1_2_and_lifo():
+    a = mc.mc_kv_allocator_create(8)
+    assert mc.mc_kv_alloc_pages(a, 3) == [0, 1, 2]
+    mc.mc_kv_free_pages(a, [1, 0])
+    assert mc.mc_kv_alloc_pages(a, 3) == [0, 1, 3]
+    with pytest.raises(mc.McError):
+        mc.mc_kv_alloc_pages(a, 5)
+    assert mc.mc_kv_allocator_num_free(a) == 4
+    mc.mc_kv_allocator_destroy(a)
+
+
+def test_check_page_table():
+    assert mc.mc_kv_check_page_table([3, 1, 2], 4) == mc.MC_OK
+    assert mc.mc_kv_check_page_table([3, 1, 3], 4) == mc.MC_ERR_ALIAS
+    assert mc.mc_kv_check_page_table([4], 4) == mc.MC_ERR_RANGE
+    assert mc.mc_kv_check_page_table([-1], 4) == mc.MC_ERR_RANGE
+    assert mc.mc_kv_check_page_table([], 4) == mc.MC_OK
+
+
+def _pool(**kw):
+    d = dict(base=FAKE, num_layers=2, num_pages=8, num_kv_heads=8, dtype=mc.MC_BF16)
+    d.update(kw)
+    return mc.pool_desc(d.pop("base"), d.pop("num_layers"), d.pop("num_pages"),
+                        d.pop("num_kv_heads"), d.pop("dtype"), **d)
+
+
+def _status(fn, *args):
+    try:
+        fn(*args, stream=0)
+    except mc.McError as e:
+        return e.status
+    return mc.MC_OK
+
+
+def test_validation_rejects_before_launch():
+    ok = _pool()
+    pk = mc.mc_kv_pack_range
+    assert _status(pk, _pool(head_dim=64), 0, 1, FAKE, 4, 0, 16, FAKE) == mc.MC_ERR_UNSUPPORTED
+    assert _status(pk, _pool(page_size=32), 0, 1, FAKE, 4, 0, 16, FAKE) == mc.MC_ERR_UNSUPPORTED
+    assert _status(pk, _pool(dtype=7), 0, 1, FAKE, 4, 0, 16, FAKE) == mc.MC_ERR_UNSUPPORTED
+    assert _status(pk, _pool(base=0), 0, 1, FAKE, 4, 0, 16, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pk, _pool(base=FAKE + 2), 0, 1, FAKE, 4, 0, 16, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pk, ok, 0, 3, FAKE, 4, 0, 16, FAKE) == mc.MC_ERR_RANGE      # layer_end > L
+    assert _status(pk, ok, 1, 0, FAKE, 4, 0, 16, FAKE) == mc.MC_ERR_RANGE      # reversed layers
+    assert _status(pk, ok, 0, 1, FAKE, 4, 9, 8, FAKE) == mc.MC_ERR_RANGE       # s0 > s1
+    assert _status(pk, ok, 0, 1, FAKE, 4, 0, 65, FAKE) == mc.MC_ERR_RANGE      # table too short
+    assert _status(pk, ok, 0, 1, None, 4, 0, 16, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pk, ok, 0, 1, FAKE, 4, 0, 16, FAKE + 8) == mc.MC_ERR_INVALID
+    # empty ranges are fine and launch nothing
+    assert _status(pk, ok, 0, 1, FAKE, 4, 5, 5, FAKE) == mc.MC_OK
+    assert _status(mc.mc_kv_unpack_range, ok, 1, 1, FAKE, 4, 0, 16, FAKE) == mc.MC_OK
+    ap = mc.mc_kv_append
+    assert _status(ap, ok, 2, FAKE, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE) == mc.MC_ERR_RANGE
+    assert _status(ap, ok, 0, None, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE) == mc.MC_ERR_INVALID
+    assert _status(ap, ok, 0, FAKE, FAKE, 1, -1, FAKE, FAKE, FAKE, FAKE) == mc.MC_ERR_INVALID
+    assert _status(ap, ok, 0, FAKE, FAKE, 1, 0, FAKE, FAKE, FAKE, FAKE) == mc.MC_OK
+    at = mc.mc_prefix_prefill_attn
+    base = [ok, 0, FAKE, 32, 1, 16, FAKE, FAKE, FAKE, FAKE, 0.0, FAKE, FAKE, FAKE, 1 << 20]
+
+    def attn(kw):
+        a = list(base)
+        for k, v in kw.items():
+            a[k] = v
+        return _status(at, *a)
+    assert attn({3: 24}) == mc.MC_ERR_UNSUPPORTED     # 24 q heads over 8 kv heads: G = 3
+    assert attn({3: 12}) == mc.MC_ERR_UNSUPPORTED     # not a multiple
+    assert attn({1: 2}) == mc.MC_ERR_RANGE            # layer
+    assert attn({10: -1.0}) == mc.MC_ERR_INVALID      # negative scale
+    assert attn({10: float("nan")}) == mc.MC_ERR_INVALID
+    assert attn({14: 16}) == mc.MC_ERR_INVALID        # workspace too small
+    assert attn({11: None}) == mc.MC_ERR_INVALID
+    assert attn({5: 0}) == mc.MC_OK                   # no new tokens: nothing to do
+    pl = mc.mc_attn_plan
+    assert _status(pl, ok, 32, 1, 16, FAKE, FAKE, FAKE, FAKE, FAKE, 8) == mc.MC_ERR_INVALID
+    assert _status(pl, ok, 32, 1, 16, FAKE, FAKE, FAKE, FAKE, None, 1 << 20) == mc.MC_ERR_INVALID
+
+
+def test_workspace_size():
+    assert mc.mc_attn_workspace_size(1, 16, 32, 8) >= 64 + 8
+    assert mc.mc_attn_workspace_size(8, 20000, 32, 8) < (1 << 20)
+    assert mc.mc_attn_workspace_size(1, 16, 24, 8) == 0
+    assert mc.mc_attn_workspace_size(-1, 16, 32, 8) == 0
+    s1 = mc.mc_attn_workspace_size(4, 1000, 32, 8)
+    s2 = mc.mc_attn_workspace_size(4, 2000, 32, 8)
+    assert s2 > s1 and s1 % 16 == 0
