@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged KV-cache hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of the Llama-3-8B-shaped
+workload (8 sequences, prompts in [1024, 4096], up to 75 % cached): page
+allocation for the new tokens (host), KV append of the new tokens, the plan
+(begin_forward), prefix-prefill attention with LSE, then pack of every sequence's
+KV into a contiguous buffer and unpack into a second page pool.  All inputs are
+resident in HBM before the timed region.  One JSON line goes to stdout.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16/fp16 MFMA, published
+HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--seed", type=int, default=2000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-copy-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; the path has no cross-GPU step "
+              "(run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import mc_inputs as mi
+    import paper_2412_12488_amd as mc
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+
+    def up(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+
+    w = mi.config(2, seed=args.seed)
+    B, Hq, Hkv, D = w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim
+    total_q = int(w.cu_q[-1])
+    flops = w.useful_flops()
+
+    # ---- resident inputs -------------------------------------------------------
+    pool_elems = w.num_pages * 2 * Hkv * 16 * D
+    pool_a = torch.zeros(pool_elems, dtype=torch.int16, device=dev)
+    pool_b = torch.zeros(pool_elems, dtype=torch.int16, device=dev)
+    desc_a = mc.pool_desc(pool_a, 1, w.num_pages, Hkv, w.dtype)
+    desc_b = mc.pool_desc(pool_b, 1, w.num_pages, Hkv, w.dtype)
+    kv = [w.kv(s) for s in range(B)]
+    q_new = up(np.concatenate([w.q(s) for s in range(B)]))
+    k_new = up(np.concatenate([kv[s][0][w.b[s]:] for s in range(B)]))
+    v_new = up(np.concatenate([kv[s][1][w.b[s]:] for s in range(B)]))
+    cu_q, begin = up(w.cu_q), up(w.b.astype(np.int32))
+    table, cu_pages = up(w.flat_page_table), up(w.cu_pages)
+    tables_a = [up(t) for t in w.page_tables]
+    trng = mi.rng_for(args.seed, 77)
+    tables_b_np = mi.scatter_page_tables(trng, w.num_pages, w.n)
+    tables_b = [up(t) for t in tables_b_np]
+    send = [torch.empty(2 * int(w.n[s]) * Hkv * D, dtype=torch.int16, device=dev) for s in range(B)]
+    # the cached prefixes [0, b) are already in the cache when a step starts
+    wp = w.with_ranges(np.zeros_like(w.b), w.b)
+    if int(wp.cu_q[-1]):
+        mc.mc_kv_append(desc_a, 0, up(np.concatenate([kv[s][0][: w.b[s]] for s in range(B)])),
+                        up(np.concatenate([kv[s][1][: w.b[s]] for s in range(B)])), B,
+                        int(wp.cu_q[-1]), up(wp.cu_q), up(wp.b.astype(np.int32)), table, cu_pages)
+    ws_bytes = mc.mc_attn_workspace_size(B, total_q, Hq, Hkv)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    out = torch.empty((total_q, Hq, D), dtype=torch.int16, device=dev)
+    lse = torch.empty((total_q, Hq), dtype=torch.float32, device=dev)
+    alloc = mc.mc_kv_allocator_create(w.num_pages)
+    new_pages = [-(-int(w.n[s]) // 16) - int(w.b[s]) // 16 for s in range(B)]
+    torch.cuda.synchronize()
+
+    attn_events = []
+
+    def step(record):
+        # a1: page reservation for the new tokens (host free list; ids from the seeded tables
+        # are the ones the kernels use, so the step is repeatable)
+        got = [mc.mc_kv_alloc_pages(alloc, n) for n in new_pages]
+        for g in reversed(got):
+            mc.mc_kv_free_pages(alloc, g[::-1])
+        # a2: append the new tokens' K/V
+        mc.mc_kv_append(desc_a, 0, k_new, v_new, B, total_q, cu_q, begin, table, cu_pages)
+        # begin_forward + a3: attention of the new range over cache + itself
+        mc.mc_attn_plan(desc_a, Hq, B, total_q, cu_q, begin, table, cu_pages, ws, ws_bytes)
+        if record:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        mc.mc_prefix_prefill_attn(desc_a, 0, q_new, Hq, B, total_q, cu_q, begin, table, cu_pages,
+                                  0.0, out, lse, ws, ws_bytes)
+        if record:
+            e1.record()
+            attn_events.append((e0, e1))
+        # a4 + a5: ship every sequence's KV [0, n) to the second pool
+        for s in range(B):
+            n = int(w.n[s])
+            mc.mc_kv_pack_range(desc_a, 0, 1, tables_a[s], len(w.page_tables[s]), 0, n, send[s])
+            mc.mc_kv_unpack_range(desc_b, 0, 1, tables_b[s], len(tables_b_np[s]), 0, n, send[s])
+
+    for _ in range(args.warmup):
+        step(False)
+    mc.mc_attn_plan_check(ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in attn_events]))
+    attn_tflops = flops / (attn_ms * 1e-3) / 1e12
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    def timed(fn, iters=20, warm=3):
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    # ---- copies, each alone: this workload, then the long-context transfer size ----
+    copy = {}
+    kv_bytes = int(np.sum(w.n)) * w.token_bytes
+    new_bytes = total_q * w.token_bytes
+    ms = timed(lambda: mc.mc_kv_append(desc_a, 0, k_new, v_new, B, total_q, cu_q, begin, table,
+                                       cu_pages))
+    copy["append_GBps"] = round(2 * new_bytes / ms / 1e6, 1)
+
+    def pack_all():
+        for s in range(B):
+            mc.mc_kv_pack_range(desc_a, 0, 1, tables_a[s], len(w.page_tables[s]), 0, int(w.n[s]),
+                                send[s])
+
+    def unpack_all():
+        for s in range(B):
+            mc.mc_kv_unpack_range(desc_b, 0, 1, tables_b[s], len(tables_b_np[s]), 0, int(w.n[s]),
+                                  send[s])
+    copy["pack_GBps"] = round(2 * kv_bytes / timed(pack_all) / 1e6, 1)
+    copy["unpack_GBps"] = round(2 * kv_bytes / timed(unpack_all) / 1e6, 1)
+    copy["payload_MiB"] = round(kv_bytes / 2**20, 1)
+    if not args.no_copy_sweep:
+        # 32768 tokens x 32 layers = 4 GiB of KV between two pools (long-context transfer)
+        del pool_a, pool_b, send
+        torch.cuda.empty_cache()
+        L, T = 32, 32768
+        npg = T // 16
+        big = L * npg * 2 * Hkv * 16 * D
+        big_a = torch.empty(big, dtype=torch.int16, device=dev)
+        big_b = torch.empty(big, dtype=torch.int16, device=dev)
+        big_a.view(torch.int32).random_()
+        big_s = torch.empty(big, dtype=torch.int16, device=dev)
+        da = mc.pool_desc(big_a, L, npg, Hkv, w.dtype)
+        dbb = mc.pool_desc(big_b, L, npg, Hkv, w.dtype)
+        ta = up(mi.rng_for(args.seed, 78).permutation(npg).astype(np.int32))
+        tb = up(mi.rng_for(args.seed, 79).permutation(npg).astype(np.int32))
+        payload = L * T * w.token_bytes
+        ms_p = timed(lambda: mc.mc_kv_pack_range(da, 0, L, ta, npg, 0, T, big_s), iters=10)
+        ms_u = timed(lambda: mc.mc_kv_unpack_range(dbb, 0, L, tb, npg, 0, T, big_s), iters=10)
+        ms_c = timed(lambda: big_b.copy_(big_a), iters=10)
+        copy["long_context"] = {
+            "payload_GiB": payload / 2**30,
+            "pack_GBps": round(2 * payload / ms_p / 1e6, 1),
+            "unpack_GBps": round(2 * payload / ms_u / 1e6, 1),
+            "pack_frac_of_hbm_peak": round(2 * payload / ms_p / 1e6 / HBM_PEAK_GBS, 3),
+            "unpack_frac_of_hbm_peak": round(2 * payload / ms_u / 1e6 / HBM_PEAK_GBS, 3),
+            "plain_copy_GBps": round(2 * payload / ms_c / 1e6, 1),
+        }
+        del big_a, big_b, big_s
+
+    # ---- CPU oracle on this machine's host cores, bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        shape = oracle.Shape(1, w.num_pages, 16, Hkv, D, w.dtype)
+        opool = oracle.new_pool(shape)
+        for s in range(B):
+            oracle.append(opool, shape, 0, kv[s][0], kv[s][1], 0, w.page_tables[s])
+        cores = len(os.sched_getaffinity(0))
+        omp = int(os.environ.get("OMP_NUM_THREADS", cores))
+        t_cpu = 0.0
+        for s in range(B):
+            qs = w.q(s)
+            c0 = time.perf_counter()
+            oracle.attention(opool, shape, 0, w.page_tables[s], qs, Hq, int(w.b[s]), int(w.n[s]))
+            t_cpu += time.perf_counter() - c0
+        cpu = {"value": round(flops / t_cpu / 1e12, 6), "unit": "TFLOP/s",
+               "cores": min(cores, omp), "kind": "oracle",
+               "sample": f"attention of the whole workload (all {total_q} new rows x {Hq} heads, "
+                         f"{B} sequences), fp64 C/OpenMP oracle, {t_cpu:.1f} s; copies not timed"}
+
+    result = {
+        "metric": "prefix-prefill attention TFLOP/s (% MFMA peak); KV pack/unpack GB/s (% HBM)",
+        "value": round(value, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-3-8B layer, bf16, 32 q heads / 8 kv heads, "
+                               "head_dim 128, page 16, batch 8, prompts U[1024,4096], cached "
+                               "fraction U[0,0.75], pages scattered in a 65536-page pool",
+                   "seed": args.seed, "total_new_tokens": total_q,
+                   "total_tokens": int(np.sum(w.n)),
+                   "useful_attention_flops_per_step": flops,
+                   "step": "alloc + append + plan + attention + pack + unpack"},
+        "roofline": {"kernel": "attn_kernel<bf16, G=4>", "bound": "mfma",
+                     "achieved": round(attn_tflops, 2), "peak": MFMA_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(attn_tflops / MFMA_PEAK_TFLOPS, 4),
+                     "traffic": None, "avg_launch_ms": round(attn_ms, 4)},
+        "copy": copy,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
