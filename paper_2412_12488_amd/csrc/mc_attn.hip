@@ -21,6 +21,8 @@
 //     reads (V) spread over all banks.
 #include <math.h>
 
+#include <type_traits>
+
 #include "mc_common.h"
 
 namespace {
@@ -256,6 +258,13 @@ struct AttnArgs {
 };
 
 typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* gbl_void_ptr;
+// Read-only metadata is addressed through the constant address space so that wave-uniform
+// reads stay scalar loads (no vector-memory counter involved) even after LDS copies and stores.
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+
+constexpr int kTileBytes = kBN * kRowBytes;   // one K or V tile in LDS: 16 KiB
 
 // LDS tile: 64 rows (keys) x 256 B.  16-byte chunk c of row r sits at chunk position
 //   K: c ^ (r & 15)        -> 16 lanes reading one chunk of 16 consecutive rows hit 16 positions
@@ -263,12 +272,18 @@ typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 __device__ __forceinline__ int k_swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ (row & 15)) << 4); }
 __device__ __forceinline__ int v_swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row & 3) << 2)) << 4); }
 
+// Pipeline of one workgroup (one barrier per KV tile):
+//   iteration j   issues the global->LDS copies of K(j+2) and V(j+1)   (asynchronous, no VGPRs)
+//                 finds the row max of S(j), rescales O only if the max moved far
+//                 computes S(j+1) = K(j+1) Q^T on the MFMA pipe while the VALU does the
+//                 exponentials of S(j), then O^T += V(j)^T P(j)^T
+//   so K is always one tile ahead of V, and two LDS buffers of each are enough.
 template <typename T, int G>
 __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   constexpr int TOK = kBM / G;  // tokens per q tile
   typedef typename Mfma<T>::vec8 vec8;
-  __shared__ __attribute__((aligned(16))) char lds_k[kBN * kRowBytes];
-  __shared__ __attribute__((aligned(16))) char lds_v[kBN * kRowBytes];
+  __shared__ __attribute__((aligned(1024))) char lds_k[2 * kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char lds_v[2 * kTileBytes];
 
   const int hk = blockIdx.x % a.hkv;
   const int wi = blockIdx.x / a.hkv;
@@ -277,7 +292,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
       a.hdr->batch != a.batch || a.hdr->total_q != a.total_q)
     return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
 
   const int seq = a.tile_seq[wi], row0 = a.tile_row0[wi];
@@ -286,7 +302,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const int first_pos = b + row0;                    // position of the tile's first token
   const int kv_len = first_pos + ntok;               // keys [0, kv_len) are needed
   const int n_kv_tiles = (kv_len + kBN - 1) / kBN;
-  const int32_t* table = a.page_table + a.cu_pages[seq];
+  const int last_pidx = (kv_len - 1) / kPage;        // last table entry that holds a needed key
+  const_i32_ptr table = (const_i32_ptr)(a.page_table + a.cu_pages[seq]);
 
   // this lane's query row
   const int r = wave * 32 + l32;                     // row in tile, head-major
@@ -304,34 +321,47 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     qreg[kk] = __builtin_bit_cast(vec8, v);
   }
 
-  // global -> register staging of one KV tile: pass i moves page i of the tile,
-  // thread tid moves bytes [16 tid, 16 tid + 16) of the page's 4 KiB K run and V run
-  const int ld_slot = tid >> 4, ld_chunk = tid & 15;
-  const int64_t head_off_k = (int64_t)hk * kHeadPageBytes + tid * 16;
-  const int64_t head_off_v = (int64_t)(a.hkv + hk) * kHeadPageBytes + tid * 16;
-  u32x4 stage_k[4], stage_v[4];
-  auto load_tile = [&](int jt) {
+  // ---- global -> LDS copies (no VGPR staging) -------------------------------------
+  // A wavefront's copy instruction fills 1 KiB of LDS linearly (lane L -> bytes 16 L..),
+  // i.e. 4 tile rows.  Copy i of wave w fills rows 16 i + 4 w + L/16 (page i of the tile,
+  // slots 4 w..4 w+3); lane L fetches the 16-byte chunk that the swizzle wants at position
+  // L%16 of that row.  Keys at or beyond kv_len (unwritten slots, pages past the table's
+  // needed part) are replaced by the last needed key: finite data that the mask discards.
+  const int ld_slot = 4 * wave + (lane >> 4), ld_pos = lane & 15;
+  const int k_chunk_off = ((ld_pos ^ ld_slot) << 4);
+  const int v_chunk_off = ((ld_pos ^ ((ld_slot & 3) << 2)) << 4);
+  const char* pool_k = a.pool_layer + (int64_t)hk * kHeadPageBytes;
+  const char* pool_v = a.pool_layer + (int64_t)(a.hkv + hk) * kHeadPageBytes;
+  auto issue_tile = [&](int jt, bool is_v, char* lds_tile) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int key = jt * kBN + i * kPage + ld_slot;
-      u32x4 kk4 = {0, 0, 0, 0}, vv4 = {0, 0, 0, 0};
-      if (key < kv_len) {
-        int32_t page = table[jt * 4 + i];
-        page = min(max(page, 0), a.num_pages - 1);   // the plan has checked; stay in bounds anyway
-        const char* p = a.pool_layer + page * a.page_stride;
-        kk4 = *reinterpret_cast<const u32x4*>(p + head_off_k);
-        vv4 = *reinterpret_cast<const u32x4*>(p + head_off_v);
-      }
-      stage_k[i] = kk4;
-      stage_v[i] = vv4;
+      const int pidx = min(jt * 4 + i, last_pidx);
+      int32_t page = table[pidx];
+      page = min(max(page, 0), a.num_pages - 1);   // the plan has checked; stay in bounds anyway
+      const int slot = min(ld_slot, kv_len - 1 - pidx * kPage);
+      const char* src = (is_v ? pool_v : pool_k) + page * a.page_stride + slot * kRowBytes +
+                        (is_v ? v_chunk_off : k_chunk_off);
+      __builtin_amdgcn_global_load_lds((gbl_void_ptr)src,
+                                       (lds_void_ptr)(lds_tile + i * 4096 + wave * 1024), 16, 0, 0);
     }
   };
-  auto store_tile = [&]() {
+  auto wait_copies_and_sync = [&]() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  };
+
+  // ---- S^T = K Q^T for one tile: two 32-key chunks ----------------------------------
+  auto qk_tile = [&](const char* ktile, f32x16 (&s_acc)[2]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = i * kPage + ld_slot;
-      *reinterpret_cast<u32x4*>(lds_k + k_swz(row, ld_chunk)) = stage_k[i];
-      *reinterpret_cast<u32x4*>(lds_v + v_swz(row, ld_chunk)) = stage_v[i];
+    for (int c = 0; c < 2; ++c) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_acc[c][i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const int row = c * 32 + l32;
+        vec8 kfrag = *reinterpret_cast<const vec8*>(ktile + k_swz(row, 2 * kk + half));
+        s_acc[c] = Mfma<T>::run(kfrag, qreg[kk], s_acc[c]);
+      }
     }
   };
 
@@ -340,73 +370,76 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   for (int dc = 0; dc < 4; ++dc)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o_acc[dc][i] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;   // running max (raw scores) and this lane's partial sum
+  float m_run = -INFINITY, l_run = 0.f;   // reference max (raw scores), this lane's partial sum
   const float c2 = a.scale_log2;
-
   // per-lane constants of the transposing V read: 16-lane group gq, lane j in group
   const int j16 = lane & 15, gq = (lane >> 4) & 1;
 
-  load_tile(0);
-  for (int jt = 0; jt < n_kv_tiles; ++jt) {
-    __syncthreads();               // every wave is done reading the previous tile
-    store_tile();
-    __syncthreads();
-    if (jt + 1 < n_kv_tiles) load_tile(jt + 1);   // in flight while this tile is computed
+  f32x16 s_cur[2];
+  issue_tile(0, false, lds_k);
+  issue_tile(0, true, lds_v);
+  wait_copies_and_sync();
+  qk_tile(lds_k, s_cur);
+  issue_tile(min(1, n_kv_tiles - 1), false, lds_k + kTileBytes);
+  wait_copies_and_sync();
 
-    // ---- S^T = K Q^T : two 32-key chunks ----
-    f32x16 s_acc[2];
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s_acc[c][i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const int row = c * 32 + l32;
-        vec8 kfrag = *reinterpret_cast<const vec8*>(lds_k + k_swz(row, 2 * kk + half));
-        s_acc[c] = Mfma<T>::run(kfrag, qreg[kk], s_acc[c]);
-      }
+  // One KV tile.  MASK: the tile reaches the causal diagonal.  HAS_NEXT: tile j+1 exists.
+  auto body = [&](int jt, auto mask_tag, auto next_tag) {
+    constexpr bool MASK = decltype(mask_tag)::value;
+    constexpr bool HAS_NEXT = decltype(next_tag)::value;
+    const int par = jt & 1;
+    if (HAS_NEXT) {
+      issue_tile(min(jt + 2, n_kv_tiles - 1), false, lds_k + par * kTileBytes);
+      issue_tile(jt + 1, true, lds_v + (par ^ 1) * kTileBytes);
     }
     // key held by accumulator register i of chunk c: jt*64 + 32c + 8(i/4) + 4 half + i%4
-    if (jt * kBN + kBN - 1 > first_pos) {          // tile reaches the causal diagonal
+    if (MASK) {
 #pragma unroll
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int key = jt * kBN + c * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-          if (key > my_pos) s_acc[c][i] = -INFINITY;
+          if (key > my_pos) s_cur[c][i] = -INFINITY;
         }
     }
-    // ---- online softmax ----
-    float mx = s_acc[0][0];
+    // ---- row max; move the reference max (and rescale O, l) only when some row's max
+    //      rose by more than 2^8 in the exp2 domain: p stays below 2^8, sums stay exact
+    float mx = s_cur[0][0];
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[c][i]);
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_cur[c][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-    const float mc2 = m_new * c2;
-    m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64((mx - m_run) * c2 > 8.f) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[dc][i] *= alpha;
+    }
+    const float mc2 = m_run * c2;
+    // ---- S(j+1) on the MFMA pipe, exponentials of S(j) on the VALU ----
+    f32x16 s_next[2];
+    if (HAS_NEXT) qk_tile(lds_k + (par ^ 1) * kTileBytes, s_next);
     float psum = 0.f;
     uint32_t p_pk[2][8];
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[c][i], c2, -mc2));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[c][i + 1], c2, -mc2));
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[c][i], c2, -mc2));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[c][i + 1], c2, -mc2));
         psum += p0 + p1;
         p_pk[c][i >> 1] = Mfma<T>::pack2(p0, p1);
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int dc = 0; dc < 4; ++dc)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o_acc[dc][i] *= alpha;
-
+    l_run += psum;
     // ---- O^T += V^T P^T ----
     // k-step (c, s) covers accumulator registers 8s..8s+7 of chunk c, i.e. for this
     // lane-half the keys 32c + 16s + {0..3} + 4 half and 32c + 16s + 8 + {0..3} + 4 half
+    const char* vtile = lds_v + par * kTileBytes;
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -420,32 +453,54 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
           const int chunk = dc * 4 + gq * 2 + ((j16 & 3) >> 1);
           const int sub = (j16 & 1) * 8;
           s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(lds_v + v_swz(key_lo, chunk) + sub));
+              (lds_s16x4_ptr)(vtile + v_swz(key_lo, chunk) + sub));
           s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(lds_v + v_swz(key_lo + 8, chunk) + sub));
+              (lds_s16x4_ptr)(vtile + v_swz(key_lo + 8, chunk) + sub));
           s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           o_acc[dc] = Mfma<T>::run(__builtin_bit_cast(vec8, both), pfrag, o_acc[dc]);
         }
       }
-  }
+    if (HAS_NEXT) {
+      s_cur[0] = s_next[0];
+      s_cur[1] = s_next[1];
+    }
+    wait_copies_and_sync();
+  };
 
-  // ---- epilogue: normalise, write O and LSE ----
+  // tiles entirely below the diagonal need no mask: tile j is fully visible to every row
+  // iff 64 (j+1) <= first_pos + 1
+  const int n_full = min((first_pos + 1) / kBN, n_kv_tiles - 1);
+  int jt = 0;
+  for (; jt < n_full; ++jt) body(jt, std::false_type{}, std::true_type{});
+  for (; jt < n_kv_tiles - 1; ++jt) body(jt, std::true_type{}, std::true_type{});
+  body(jt, std::true_type{}, std::false_type{});
+
+  // ---- epilogue: normalise, stage O through LDS for full-row stores, write LSE ----
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv = 1.f / l_tot;
-  if (row_ok) {
-    char* o_row = a.out + q_row;
+  char* stage = lds_k + wave * (32 * kRowBytes);   // 8 KiB per wave; all tiles are consumed
 #pragma unroll
-    for (int dc = 0; dc < 4; ++dc)
+  for (int dc = 0; dc < 4; ++dc)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        // registers 4j..4j+3 hold d = 32 dc + 8 j + 4 half + {0..3}
-        u32x2 w;
-        w[0] = Mfma<T>::pack2(o_acc[dc][4 * j] * inv, o_acc[dc][4 * j + 1] * inv);
-        w[1] = Mfma<T>::pack2(o_acc[dc][4 * j + 2] * inv, o_acc[dc][4 * j + 3] * inv);
-        *reinterpret_cast<u32x2*>(o_row + (32 * dc + 8 * j + 4 * half) * 2) = w;
-      }
-    if (half == 0)
-      a.lse[(int64_t)(q0 + row0 + tt) * a.hq + hk * G + g] = m_run * a.scale + __logf(l_tot);
+    for (int j = 0; j < 4; ++j) {
+      // registers 4j..4j+3 hold d = 32 dc + 8 j + 4 half + {0..3}: 8 bytes of chunk 4 dc + j
+      u32x2 w;
+      w[0] = Mfma<T>::pack2(o_acc[dc][4 * j] * inv, o_acc[dc][4 * j + 1] * inv);
+      w[1] = Mfma<T>::pack2(o_acc[dc][4 * j + 2] * inv, o_acc[dc][4 * j + 3] * inv);
+      *reinterpret_cast<u32x2*>(stage + k_swz(l32, 4 * dc + j) + half * 8) = w;
+    }
+  if (row_ok && half == 0)
+    a.lse[(int64_t)(q0 + row0 + tt) * a.hq + hk * G + g] = m_run * a.scale + __logf(l_tot);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int lr = 4 * i + (lane >> 4);               // row of this wave's 32
+    const int rr = wave * 32 + lr, gg = rr / TOK, t2 = rr % TOK;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + k_swz(lr, lane & 15));
+    if (t2 < ntok)
+      *reinterpret_cast<u32x4*>(a.out + ((int64_t)(q0 + row0 + t2) * a.hq + hk * G + gg) * kRowBytes +
+                                (lane & 15) * 16) = v;
   }
 }
 
