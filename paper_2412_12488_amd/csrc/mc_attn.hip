@@ -266,6 +266,20 @@ typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
 
 constexpr int kTileBytes = kBN * kRowBytes;   // one K or V tile in LDS: 16 KiB
 
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(size_t)(lds_void_ptr)(p);
+}
+
+// Asynchronous 16-byte-per-lane copy from global memory straight into LDS: lane L's bytes
+// land at lds_base + 16 L.  base and lds_base are wave-uniform.  Issued as inline assembly so
+// that the compiler does not serialise it against later LDS reads of OTHER buffers; completion
+// is awaited explicitly (s_waitcnt vmcnt(0)) before the workgroup barrier that publishes it.
+__device__ __forceinline__ void copy16_to_lds(const char* base, uint32_t lane_off,
+                                              uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(lane_off), "s"(base), "s"(lds_base) : "memory", "m0");
+}
+
 // LDS tile: 64 rows (keys) x 256 B.  16-byte chunk c of row r sits at chunk position
 //   K: c ^ (r & 15)        -> 16 lanes reading one chunk of 16 consecutive rows hit 16 positions
 //   V: c ^ ((r & 3) << 2)  -> a transposing read of 4 consecutive rows x 64 B hits 16 positions
@@ -328,21 +342,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   // L%16 of that row.  Keys at or beyond kv_len (unwritten slots, pages past the table's
   // needed part) are replaced by the last needed key: finite data that the mask discards.
   const int ld_slot = 4 * wave + (lane >> 4), ld_pos = lane & 15;
-  const int k_chunk_off = ((ld_pos ^ ld_slot) << 4);
-  const int v_chunk_off = ((ld_pos ^ ((ld_slot & 3) << 2)) << 4);
+  const uint32_t k_chunk_off = ((ld_pos ^ ld_slot) << 4);
+  const uint32_t v_chunk_off = ((ld_pos ^ ((ld_slot & 3) << 2)) << 4);
   const char* pool_k = a.pool_layer + (int64_t)hk * kHeadPageBytes;
   const char* pool_v = a.pool_layer + (int64_t)(a.hkv + hk) * kHeadPageBytes;
+  const uint32_t page_blocks = 2u * a.hkv;     // 4 KiB blocks per page
   auto issue_tile = [&](int jt, bool is_v, char* lds_tile) {
+    int32_t pg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pg[i] = table[min(jt * 4 + i, last_pidx)];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int pidx = min(jt * 4 + i, last_pidx);
-      int32_t page = table[pidx];
-      page = min(max(page, 0), a.num_pages - 1);   // the plan has checked; stay in bounds anyway
-      const int slot = min(ld_slot, kv_len - 1 - pidx * kPage);
-      const char* src = (is_v ? pool_v : pool_k) + page * a.page_stride + slot * kRowBytes +
-                        (is_v ? v_chunk_off : k_chunk_off);
-      __builtin_amdgcn_global_load_lds((gbl_void_ptr)src,
-                                       (lds_void_ptr)(lds_tile + i * 4096 + wave * 1024), 16, 0, 0);
+      const uint32_t page = (uint32_t)min(max(pg[i], 0), a.num_pages - 1);  // plan-checked; stay in bounds
+      const char* base = (is_v ? pool_v : pool_k) + ((uint64_t)(page * page_blocks) << 12);  // uniform
+      const uint32_t slot = (uint32_t)min(ld_slot, kv_len - 1 - pidx * kPage);
+      const uint32_t lane_off = slot * kRowBytes + (is_v ? v_chunk_off : k_chunk_off);
+      copy16_to_lds(base, lane_off, lds_addr(lds_tile) + i * 4096 + wave * 1024);
     }
   };
   auto wait_copies_and_sync = [&]() {
@@ -375,43 +391,51 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   // per-lane constants of the transposing V read: 16-lane group gq, lane j in group
   const int j16 = lane & 15, gq = (lane >> 4) & 1;
 
+  // key held by accumulator register i of chunk c of tile jt: 64 jt + 32 c + 8 (i/4) + 4 half + i%4
+  auto mask_tile = [&](int jt, f32x16 (&s)[2]) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = jt * kBN + c * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+        if (key > my_pos) s[c][i] = -INFINITY;
+      }
+  };
+  auto row_max = [&](const f32x16 (&s)[2]) {
+    float mx = s[0][0];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[c][i]);
+    return fmaxf(mx, __shfl_xor(mx, 32));
+  };
+
+  // tile j is fully visible to every row of the q tile iff 64 (j+1) <= first_pos + 1
+  const int n_full = (first_pos + 1) / kBN;
+
   f32x16 s_cur[2];
   issue_tile(0, false, lds_k);
   issue_tile(0, true, lds_v);
   wait_copies_and_sync();
   qk_tile(lds_k, s_cur);
   issue_tile(min(1, n_kv_tiles - 1), false, lds_k + kTileBytes);
+  if (n_full == 0) mask_tile(0, s_cur);
+  float mx_cur = row_max(s_cur);
   wait_copies_and_sync();
 
-  // One KV tile.  MASK: the tile reaches the causal diagonal.  HAS_NEXT: tile j+1 exists.
+  // One KV tile.  HAS_NEXT: tile j+1 exists; MASK_NEXT: it reaches the causal diagonal.
   auto body = [&](int jt, auto mask_tag, auto next_tag) {
-    constexpr bool MASK = decltype(mask_tag)::value;
+    constexpr bool MASK_NEXT = decltype(mask_tag)::value;
     constexpr bool HAS_NEXT = decltype(next_tag)::value;
     const int par = jt & 1;
     if (HAS_NEXT) {
       issue_tile(min(jt + 2, n_kv_tiles - 1), false, lds_k + par * kTileBytes);
       issue_tile(jt + 1, true, lds_v + (par ^ 1) * kTileBytes);
     }
-    // key held by accumulator register i of chunk c: jt*64 + 32c + 8(i/4) + 4 half + i%4
-    if (MASK) {
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = jt * kBN + c * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-          if (key > my_pos) s_cur[c][i] = -INFINITY;
-        }
-    }
-    // ---- row max; move the reference max (and rescale O, l) only when some row's max
-    //      rose by more than 2^8 in the exp2 domain: p stays below 2^8, sums stay exact
-    float mx = s_cur[0][0];
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_cur[c][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    if (__builtin_amdgcn_ballot_w64((mx - m_run) * c2 > 8.f) != 0) {
-      const float m_new = fmaxf(m_run, mx);
+    // ---- move the reference max (and rescale O, l) only when some row's max rose by
+    //      more than 2^8 in the exp2 domain: p stays below 2^8, sums stay exact
+    if (__builtin_amdgcn_ballot_w64((mx_cur - m_run) * c2 > 8.f) != 0) {
+      const float m_new = fmaxf(m_run, mx_cur);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
       m_run = m_new;
       l_run *= alpha;
@@ -436,7 +460,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
         p_pk[c][i >> 1] = Mfma<T>::pack2(p0, p1);
       }
     l_run += psum;
-    // ---- O^T += V^T P^T ----
+    // ---- O^T += V^T P^T on the MFMA pipe, row max of S(j+1) on the VALU ----
     // k-step (c, s) covers accumulator registers 8s..8s+7 of chunk c, i.e. for this
     // lane-half the keys 32c + 16s + {0..3} + 4 half and 32c + 16s + 8 + {0..3} + 4 half
     const char* vtile = lds_v + par * kTileBytes;
@@ -461,17 +485,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
         }
       }
     if (HAS_NEXT) {
+      if (MASK_NEXT) mask_tile(jt + 1, s_next);
+      mx_cur = row_max(s_next);
       s_cur[0] = s_next[0];
       s_cur[1] = s_next[1];
     }
     wait_copies_and_sync();
   };
 
-  // tiles entirely below the diagonal need no mask: tile j is fully visible to every row
-  // iff 64 (j+1) <= first_pos + 1
-  const int n_full = min((first_pos + 1) / kBN, n_kv_tiles - 1);
   int jt = 0;
-  for (; jt < n_full; ++jt) body(jt, std::false_type{}, std::true_type{});
+  for (; jt < min(n_full, n_kv_tiles) - 1; ++jt) body(jt, std::false_type{}, std::true_type{});
   for (; jt < n_kv_tiles - 1; ++jt) body(jt, std::true_type{}, std::true_type{});
   body(jt, std::true_type{}, std::false_type{});
 
