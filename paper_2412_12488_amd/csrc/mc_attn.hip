@@ -339,27 +339,33 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   // A wavefront's copy instruction fills 1 KiB of LDS linearly (lane L -> bytes 16 L..),
   // i.e. 4 tile rows.  Copy i of wave w fills rows 16 i + 4 w + L/16 (page i of the tile,
   // slots 4 w..4 w+3); lane L fetches the 16-byte chunk that the swizzle wants at position
-  // L%16 of that row.  Keys at or beyond kv_len (unwritten slots, pages past the table's
-  // needed part) are replaced by the last needed key: finite data that the mask discards.
+  // L%16 of that row.  Rows of keys at or beyond kv_len receive whatever the page holds
+  // (K: discarded by the mask; V: zeroed in LDS before the last tile's P.V, since 0 x NaN
+  // would poison the accumulators).
   const int ld_slot = 4 * wave + (lane >> 4), ld_pos = lane & 15;
-  const uint32_t k_chunk_off = ((ld_pos ^ ld_slot) << 4);
-  const uint32_t v_chunk_off = ((ld_pos ^ ((ld_slot & 3) << 2)) << 4);
   const char* pool_k = a.pool_layer + (int64_t)hk * kHeadPageBytes;
-  const char* pool_v = a.pool_layer + (int64_t)(a.hkv + hk) * kHeadPageBytes;
+  const uint32_t k_lane_off = ld_slot * kRowBytes + ((ld_pos ^ ld_slot) << 4);
+  const uint32_t v_lane_off = ld_slot * kRowBytes + ((ld_pos ^ ((ld_slot & 3) << 2)) << 4) +
+                              (uint32_t)a.hkv * kHeadPageBytes;   // V run sits hkv blocks after K
   const uint32_t page_blocks = 2u * a.hkv;     // 4 KiB blocks per page
-  auto issue_tile = [&](int jt, bool is_v, char* lds_tile) {
-    int32_t pg[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) pg[i] = table[min(jt * 4 + i, last_pidx)];
+  // wave-uniform address of this kv head's K run in each of the 4 pages of tile jt.  Table
+  // entries past the last needed one are replaced by the last needed one.
+  struct TilePages { const char* base[4]; };
+  auto tile_pages = [&](int jt) {
+    TilePages t;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int pidx = min(jt * 4 + i, last_pidx);
-      const uint32_t page = (uint32_t)min(max(pg[i], 0), a.num_pages - 1);  // plan-checked; stay in bounds
-      const char* base = (is_v ? pool_v : pool_k) + ((uint64_t)(page * page_blocks) << 12);  // uniform
-      const uint32_t slot = (uint32_t)min(ld_slot, kv_len - 1 - pidx * kPage);
-      const uint32_t lane_off = slot * kRowBytes + (is_v ? v_chunk_off : k_chunk_off);
-      copy16_to_lds(base, lane_off, lds_addr(lds_tile) + i * 4096 + wave * 1024);
+      int32_t pg = table[min(jt * 4 + i, last_pidx)];
+      pg = min(max(pg, 0), a.num_pages - 1);       // checked by the plan; stay in bounds anyway
+      t.base[i] = pool_k + ((uint64_t)((uint32_t)pg * page_blocks) << 12);
     }
+    return t;
+  };
+  auto issue_tile = [&](const TilePages& t, bool is_v, char* lds_tile) {
+    const uint32_t dst = lds_addr(lds_tile) + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      copy16_to_lds(t.base[i], is_v ? v_lane_off : k_lane_off, dst + i * 4096);
   };
   auto wait_copies_and_sync = [&]() {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -407,21 +413,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     for (int c = 0; c < 2; ++c)
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[c][i]);
-    return fmaxf(mx, __shfl_xor(mx, 32));
+    // the other 32 keys of the row sit in lane l ^ 32: swap the wave's halves on the VALU
+    const uint32_t bits = __builtin_bit_cast(uint32_t, mx);
+    const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+    return fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
   };
 
   // tile j is fully visible to every row of the q tile iff 64 (j+1) <= first_pos + 1
   const int n_full = (first_pos + 1) / kBN;
 
   f32x16 s_cur[2];
-  issue_tile(0, false, lds_k);
-  issue_tile(0, true, lds_v);
+  TilePages pages_next = tile_pages(min(1, n_kv_tiles - 1));   // pages of tile j+1 during tile j
+  {
+    const TilePages p0 = tile_pages(0);
+    issue_tile(p0, false, lds_k);
+    issue_tile(p0, true, lds_v);
+    issue_tile(pages_next, false, lds_k + kTileBytes);
+  }
   wait_copies_and_sync();
   qk_tile(lds_k, s_cur);
-  issue_tile(min(1, n_kv_tiles - 1), false, lds_k + kTileBytes);
   if (n_full == 0) mask_tile(0, s_cur);
   float mx_cur = row_max(s_cur);
-  wait_copies_and_sync();
+  __syncthreads();   // every wave has read K(0) before the first iteration overwrites it
 
   // One KV tile.  HAS_NEXT: tile j+1 exists; MASK_NEXT: it reaches the causal diagonal.
   auto body = [&](int jt, auto mask_tag, auto next_tag) {
@@ -429,8 +442,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     constexpr bool HAS_NEXT = decltype(next_tag)::value;
     const int par = jt & 1;
     if (HAS_NEXT) {
-      issue_tile(min(jt + 2, n_kv_tiles - 1), false, lds_k + par * kTileBytes);
-      issue_tile(jt + 1, true, lds_v + (par ^ 1) * kTileBytes);
+      const TilePages pages_next2 = tile_pages(min(jt + 2, n_kv_tiles - 1));
+      issue_tile(pages_next2, false, lds_k + par * kTileBytes);
+      issue_tile(pages_next, true, lds_v + (par ^ 1) * kTileBytes);
+      pages_next = pages_next2;
+    } else if (kv_len < (jt + 1) * kBN) {
+      // last tile: zero the V rows of keys >= kv_len (their P is 0, their bytes are arbitrary)
+      const int valid = kv_len - jt * kBN;
+      const u32x4 zero = {0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 16 + (tid >> 4);
+        if (row >= valid)
+          *reinterpret_cast<u32x4*>(lds_v + par * kTileBytes + row * kRowBytes + (tid & 15) * 16) = zero;
+      }
+      __syncthreads();
     }
     // ---- move the reference max (and rescale O, l) only when some row's max rose by
     //      more than 2^8 in the exp2 domain: p stays below 2^8, sums stay exact
@@ -456,7 +482,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
       for (int i = 0; i < 16; i += 2) {
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[c][i], c2, -mc2));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[c][i + 1], c2, -mc2));
-        psum += p0 + p1;
+        psum += p0 + p1;   // the unrounded values: LSE must not inherit P's 2-byte rounding
         p_pk[c][i >> 1] = Mfma<T>::pack2(p0, p1);
       }
     l_run += psum;

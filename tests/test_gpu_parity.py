@@ -120,8 +120,11 @@ def test_transfer_then_attend_equals_local_attention():
 
 # ---------------------------------------------------------------- attention ----
 def check_attention(w, layer=0, scale=None, sample=None, seed=0):
+    # every slot that is never appended holds NaN bit patterns: unwritten slots of a
+    # sequence's last page and foreign pages must not leak into the result
     pool = DevPool(w)
-    opool = oracle.new_pool(pool.shape)
+    pool.t.fill_(0x7fc1)
+    opool = np.full(pool.elems, 0x7fc1, dtype=np.uint16)
     fill_both(w, pool, opool, layers=(layer,))
     db = DevBatch(w)
     qs = [w.q(s, layer) for s in range(w.batch)]
