@@ -351,14 +351,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   // wave-uniform address of this kv head's K run in each of the 4 pages of tile jt.  Table
   // entries past the last needed one are replaced by the last needed one.
   struct TilePages { const char* base[4]; };
-  auto tile_pages = [&](int jt) {
+  auto page_base = [&](int32_t pg) {
+    pg = min(max(pg, 0), a.num_pages - 1);         // checked by the plan; stay in bounds anyway
+    return pool_k + ((uint64_t)((uint32_t)pg * page_blocks) << 12);
+  };
+  auto tile_pages = [&](int jt) {                  // scalar reads: used before the loop only
     TilePages t;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int32_t pg = table[min(jt * 4 + i, last_pidx)];
-      pg = min(max(pg, 0), a.num_pages - 1);       // checked by the plan; stay in bounds anyway
-      t.base[i] = pool_k + ((uint64_t)((uint32_t)pg * page_blocks) << 12);
-    }
+    for (int i = 0; i < 4; ++i) t.base[i] = page_base(table[min(jt * 4 + i, last_pidx)]);
+    return t;
+  };
+  // Inside the loop the 4 page ids of a tile are fetched one iteration early by a vector
+  // load (lane i & 3 holds id i) and moved to scalar registers when the addresses are built,
+  // so no iteration waits on a page-table read.
+  const int32_t* table_g = a.page_table + a.cu_pages[seq];
+  auto fetch_ids = [&](int jt) { return table_g[min(jt * 4 + (lane & 3), last_pidx)]; };
+  auto pages_from_ids = [&](int32_t ids) {
+    TilePages t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t.base[i] = page_base(__builtin_amdgcn_readlane(ids, i));
     return t;
   };
   auto issue_tile = [&](const TilePages& t, bool is_v, char* lds_tile) {
@@ -424,6 +435,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 
   f32x16 s_cur[2];
   TilePages pages_next = tile_pages(min(1, n_kv_tiles - 1));   // pages of tile j+1 during tile j
+  int32_t ids_next2 = fetch_ids(min(2, n_kv_tiles - 1));       // ids of tile j+2 during tile j
   {
     const TilePages p0 = tile_pages(0);
     issue_tile(p0, false, lds_k);
@@ -442,10 +454,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     constexpr bool HAS_NEXT = decltype(next_tag)::value;
     const int par = jt & 1;
     if (HAS_NEXT) {
-      const TilePages pages_next2 = tile_pages(min(jt + 2, n_kv_tiles - 1));
+      const TilePages pages_next2 = pages_from_ids(ids_next2);
       issue_tile(pages_next2, false, lds_k + par * kTileBytes);
       issue_tile(pages_next, true, lds_v + (par ^ 1) * kTileBytes);
       pages_next = pages_next2;
+      ids_next2 = fetch_ids(min(jt + 3, n_kv_tiles - 1));
     } else if (kv_len < (jt + 1) * kBN) {
       // last tile: zero the V rows of keys >= kv_len (their P is 0, their bytes are arbitrary)
       const int valid = kv_len - jt * kBN;
