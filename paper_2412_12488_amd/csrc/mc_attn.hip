@@ -453,23 +453,54 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     constexpr bool MASK_NEXT = decltype(mask_tag)::value;
     constexpr bool HAS_NEXT = decltype(next_tag)::value;
     const int par = jt & 1;
+    const char* ktile = lds_k + (par ^ 1) * kTileBytes;   // K(j+1)
+    const char* vtile = lds_v + par * kTileBytes;         // V(j)
+    // Operand fragments are fetched from LDS a fixed number of MFMAs ahead of their use.
+    // QK step t (0..15): key chunk c = t & 1, d-step kk = t >> 1 (the two accumulator chains
+    // alternate).  PV step u (0..15): key chunk c = u >> 3, 16-key step s = (u >> 2) & 1,
+    // d chunk dc = u & 3 (four accumulator chains alternate); the step covers accumulator
+    // registers 8s..8s+7 of chunk c, i.e. for this lane-half the keys
+    // 32c + 16s + {0..3} + 4 half and 32c + 16s + 8 + {0..3} + 4 half.
+    constexpr int kAhead = 4;
+    auto k_frag = [&](int t) {
+      return *reinterpret_cast<const vec8*>(ktile + k_swz((t & 1) * 32 + l32, 2 * (t >> 1) + half));
+    };
+    auto v_frag = [&](int u) {
+      const int c = u >> 3, st = (u >> 2) & 1, dc = u & 3;
+      // 16-lane group reads 4 keys x 16 d; lane j supplies key (j/4), d-quad (j%4)
+      const int key_lo = c * 32 + st * 16 + 4 * half + (j16 >> 2);
+      const int chunk = dc * 4 + gq * 2 + ((j16 & 3) >> 1);
+      const int sub = (j16 & 1) * 8;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_ptr)(vtile + v_swz(key_lo, chunk) + sub));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_ptr)(vtile + v_swz(key_lo + 8, chunk) + sub));
+      return __builtin_bit_cast(vec8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    vec8 kf[kAhead], vf[kAhead];
     if (HAS_NEXT) {
+#pragma unroll
+      for (int t = 0; t < kAhead; ++t) kf[t] = k_frag(t);
       const TilePages pages_next2 = pages_from_ids(ids_next2);
       issue_tile(pages_next2, false, lds_k + par * kTileBytes);
       issue_tile(pages_next, true, lds_v + (par ^ 1) * kTileBytes);
       pages_next = pages_next2;
       ids_next2 = fetch_ids(min(jt + 3, n_kv_tiles - 1));
-    } else if (kv_len < (jt + 1) * kBN) {
-      // last tile: zero the V rows of keys >= kv_len (their P is 0, their bytes are arbitrary)
-      const int valid = kv_len - jt * kBN;
-      const u32x4 zero = {0, 0, 0, 0};
+    } else {
+      if (kv_len < (jt + 1) * kBN) {
+        // last tile: zero the V rows of keys >= kv_len (their P is 0, their bytes are arbitrary)
+        const int valid = kv_len - jt * kBN;
+        const u32x4 zero = {0, 0, 0, 0};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = i * 16 + (tid >> 4);
-        if (row >= valid)
-          *reinterpret_cast<u32x4*>(lds_v + par * kTileBytes + row * kRowBytes + (tid & 15) * 16) = zero;
+        for (int i = 0; i < 4; ++i) {
+          const int row = i * 16 + (tid >> 4);
+          if (row >= valid)
+            *reinterpret_cast<u32x4*>(lds_v + par * kTileBytes + row * kRowBytes + (tid & 15) * 16) = zero;
+        }
+        __syncthreads();
       }
-      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) vf[u] = v_frag(u);
     }
     // ---- move the reference max (and rescale O, l) only when some row's max rose by
     //      more than 2^8 in the exp2 domain: p stays below 2^8, sums stay exact
@@ -484,48 +515,47 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
         for (int i = 0; i < 16; ++i) o_acc[dc][i] *= alpha;
     }
     const float mc2 = m_run * c2;
-    // ---- S(j+1) on the MFMA pipe, exponentials of S(j) on the VALU ----
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- phase 1: S(j+1) = K(j+1) Q^T on the MFMA pipe, exponentials of S(j) on the VALU.
+    //      Each step: one MFMA, one fragment fetch for kAhead steps later, 1/16 of the softmax.
     f32x16 s_next[2];
-    if (HAS_NEXT) qk_tile(lds_k + (par ^ 1) * kTileBytes, s_next);
+    const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     float psum = 0.f;
     uint32_t p_pk[2][8];
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) {
+    for (int t = 0; t < 16; ++t) {
+      {
+        const int c = t >> 3, i = 2 * (t & 7);
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[c][i], c2, -mc2));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[c][i + 1], c2, -mc2));
         psum += p0 + p1;   // the unrounded values: LSE must not inherit P's 2-byte rounding
-        p_pk[c][i >> 1] = Mfma<T>::pack2(p0, p1);
+        p_pk[c][t & 7] = Mfma<T>::pack2(p0, p1);
       }
+      if (HAS_NEXT) {
+        s_next[t & 1] = Mfma<T>::run(kf[t % kAhead], qreg[t >> 1], t < 2 ? zero16 : s_next[t & 1]);
+        if (t + kAhead < 16) kf[t % kAhead] = k_frag(t + kAhead);
+        else vf[(t + kAhead) % kAhead] = v_frag(t + kAhead - 16);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     l_run += psum;
-    // ---- O^T += V^T P^T on the MFMA pipe, row max of S(j+1) on the VALU ----
-    // k-step (c, s) covers accumulator registers 8s..8s+7 of chunk c, i.e. for this
-    // lane-half the keys 32c + 16s + {0..3} + 4 half and 32c + 16s + 8 + {0..3} + 4 half
-    const char* vtile = lds_v + par * kTileBytes;
+    if (HAS_NEXT && MASK_NEXT) mask_tile(jt + 1, s_next);
+    // ---- phase 2: O^T += V(j)^T P(j)^T on the MFMA pipe, row max of S(j+1) on the VALU ----
+    float mx = -INFINITY;
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        u32x4 pw = {p_pk[c][4 * s], p_pk[c][4 * s + 1], p_pk[c][4 * s + 2], p_pk[c][4 * s + 3]};
-        const vec8 pfrag = __builtin_bit_cast(vec8, pw);
-        const int key_lo = c * 32 + s * 16 + 4 * half + (j16 >> 2);
-#pragma unroll
-        for (int dc = 0; dc < 4; ++dc) {
-          // 16-lane group reads 4 keys x 16 d; lane j supplies key (j/4), d-quad (j%4)
-          const int chunk = dc * 4 + gq * 2 + ((j16 & 3) >> 1);
-          const int sub = (j16 & 1) * 8;
-          s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(vtile + v_swz(key_lo, chunk) + sub));
-          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(vtile + v_swz(key_lo + 8, chunk) + sub));
-          s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o_acc[dc] = Mfma<T>::run(__builtin_bit_cast(vec8, both), pfrag, o_acc[dc]);
-        }
-      }
+    for (int u = 0; u < 16; ++u) {
+      const int c = u >> 3, st = (u >> 2) & 1, dc = u & 3;
+      u32x4 pw = {p_pk[c][4 * st], p_pk[c][4 * st + 1], p_pk[c][4 * st + 2], p_pk[c][4 * st + 3]};
+      o_acc[dc] = Mfma<T>::run(vf[u % kAhead], __builtin_bit_cast(vec8, pw), o_acc[dc]);
+      if (u + kAhead < 16) vf[u % kAhead] = v_frag(u + kAhead);
+      if (HAS_NEXT) mx = fmaxf(mx, fmaxf(s_next[u >> 3][2 * (u & 7)], s_next[u >> 3][2 * (u & 7) + 1]));
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (HAS_NEXT) {
-      if (MASK_NEXT) mask_tile(jt + 1, s_next);
-      mx_cur = row_max(s_next);
+      // the other 32 keys of the row sit in lane l ^ 32: swap the wave's halves on the VALU
+      const uint32_t bits = __builtin_bit_cast(uint32_t, mx);
+      const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+      mx_cur = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
       s_cur[0] = s_next[0];
       s_cur[1] = s_next[1];
     }
