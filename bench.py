@@ -24,6 +24,77 @@ MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16/fp16 MFMA, published
 HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
 
 
+ATTN_WORKLOADS = ["cfg2", "cfg3-passB", "cfg4", "cfg5-16k", "cfg5-32k", "paper-500-over-500",
+                  "paper-500-over-2500", "paper-500-over-4500"]
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very
+# command with the default seed (counters scaled by what a plain 4 GiB copy reads; see
+# profiles/bench_cfg2_hbm_traffic.md).  Valid only for the default workload.
+MEASURED_TRAFFIC = {"seed": 2000, "attention_bytes": int((355.7 + 79.8) * 2**20),
+                    "pack_4GiB_bytes": int((4096.2 + 4096.1) * 2**20)}
+
+
+def attention_workload(name):
+    import numpy as np
+
+    import mc_inputs as mi
+    if name == "cfg2":
+        return mi.config(2)
+    if name == "cfg3-passB":
+        return mi.config(3, num_layers=1)
+    if name == "cfg4":
+        return mi.config(4)
+    if name in ("cfg5-16k", "cfg5-32k"):
+        w = mi.config(5, num_layers=1)
+        keep = 0 if name == "cfg5-16k" else 1
+        b = np.where(np.arange(2) == keep, w.b, 0)
+        n = np.where(np.arange(2) == keep, w.n, 0)
+        return w.with_ranges(b, n, name)
+    if name.startswith("paper-500-over-"):
+        return mi.paper_point(int(name.rsplit("-", 1)[1]))
+    raise SystemExit(f"unknown workload {name}; choose from {ATTN_WORKLOADS}")
+
+
+def attention_only(name, iters):
+    """Attention kernel alone on random resident KV: one JSON line.  For rocprofv3 runs."""
+    import numpy as np
+    import torch
+
+    import paper_2412_12488_amd as mc
+    dev = "cuda:0"
+    w = attention_workload(name)
+    Hq, Hkv = w.num_q_heads, w.num_kv_heads
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    pool = torch.randn(w.num_pages * 2 * Hkv * 16 * 128, dtype=torch.bfloat16, device=dev)
+    desc = mc.pool_desc(pool, 1, w.num_pages, Hkv, w.dtype)
+    tq = int(w.cu_q[-1])
+    q = torch.randn(tq * Hq * 128, dtype=torch.bfloat16, device=dev)
+    cu_q, begin = up(w.cu_q), up(w.b.astype(np.int32))
+    table, cu_pages = up(w.flat_page_table), up(w.cu_pages)
+    wsb = mc.mc_attn_workspace_size(w.batch, tq, Hq, Hkv)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    out = torch.empty((tq, Hq, 128), dtype=torch.int16, device=dev)
+    lse = torch.empty((tq, Hq), dtype=torch.float32, device=dev)
+    mc.mc_attn_plan(desc, Hq, w.batch, tq, cu_q, begin, table, cu_pages, ws, wsb)
+    mc.mc_attn_plan_check(ws)
+    run = lambda: mc.mc_prefix_prefill_attn(desc, 0, q, Hq, w.batch, tq, cu_q, begin, table, cu_pages,
+                                            0.0, out, lse, ws, wsb)
+    for _ in range(2):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    fl = w.useful_flops()
+    print(json.dumps({"workload": w.name, "new_tokens": tq, "kv_tokens": int(np.sum(w.n)),
+                      "useful_flops": fl, "ms": round(ms, 4),
+                      "TFLOPs": round(fl / ms / 1e9, 1),
+                      "frac_of_mfma_peak": round(fl / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,6 +103,9 @@ def main():
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-sweep", action="store_true")
+    ap.add_argument("--attention-only", metavar="WORKLOAD", default=None,
+                    help="time only the attention kernel on one workload and exit (for profiling): "
+                         + ", ".join(ATTN_WORKLOADS))
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path has no cross-GPU step "
@@ -47,6 +121,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
+    if args.attention_only:
+        attention_only(args.attention_only, max(1, min(args.steps, 20)))
+        return
 
     def up(a):
         a = np.ascontiguousarray(a)
@@ -232,7 +309,17 @@ def main():
         "roofline": {"kernel": "attn_kernel<bf16, G=4>", "bound": "mfma",
                      "achieved": round(attn_tflops, 2), "peak": MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / MFMA_PEAK_TFLOPS, 4),
-                     "traffic": None, "avg_launch_ms": round(attn_ms, 4)},
+                     "traffic": MEASURED_TRAFFIC["attention_bytes"]
+                     if args.seed == MEASURED_TRAFFIC["seed"] else None,
+                     "algorithmic_bytes": 2 * total_q * Hq * D * 2 + total_q * Hq * 4
+                     + int(np.sum(w.n)) * w.token_bytes,
+                     "avg_launch_ms": round(attn_ms, 4)},
+        "roofline_copy": None if args.no_copy_sweep else {
+            "kernel": "range_copy_kernel<pack>, 32 layers x 32768 tokens", "bound": "hbm",
+            "achieved": copy["long_context"]["pack_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": copy["long_context"]["pack_frac_of_hbm_peak"],
+            "traffic": MEASURED_TRAFFIC["pack_4GiB_bytes"],
+            "algorithmic_bytes": 2 * int(copy["long_context"]["payload_GiB"] * 2**30)},
         "copy": copy,
         "cpu_baseline": cpu,
     }

@@ -286,6 +286,14 @@ __device__ __forceinline__ void copy16_to_lds(const char* base, uint32_t lane_of
 __device__ __forceinline__ int k_swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ (row & 15)) << 4); }
 __device__ __forceinline__ int v_swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row & 3) << 2)) << 4); }
 
+// max of three floats in one instruction (written as assembly: through fmaxf every score would
+// first pass a NaN-quieting instruction of its own)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Pipeline of one workgroup (one barrier per KV tile):
 //   iteration j   issues the global->LDS copies of K(j+2) and V(j+1)   (asynchronous, no VGPRs)
 //                 finds the row max of S(j), rescales O only if the max moved far
@@ -423,7 +431,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[c][i]);
+      for (int i = 0; i < 16; i += 2) mx = max3(mx, s[c][i], s[c][i + 1]);
     // the other 32 keys of the row sit in lane l ^ 32: swap the wave's halves on the VALU
     const uint32_t bits = __builtin_bit_cast(uint32_t, mx);
     const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
@@ -548,7 +556,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
       u32x4 pw = {p_pk[c][4 * st], p_pk[c][4 * st + 1], p_pk[c][4 * st + 2], p_pk[c][4 * st + 3]};
       o_acc[dc] = Mfma<T>::run(vf[u % kAhead], __builtin_bit_cast(vec8, pw), o_acc[dc]);
       if (u + kAhead < 16) vf[u % kAhead] = v_frag(u + kAhead);
-      if (HAS_NEXT) mx = fmaxf(mx, fmaxf(s_next[u >> 3][2 * (u & 7)], s_next[u >> 3][2 * (u & 7) + 1]));
+      if (HAS_NEXT) mx = max3(mx, s_next[u >> 3][2 * (u & 7)], s_next[u >> 3][2 * (u & 7) + 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (HAS_NEXT) {
