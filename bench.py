@@ -150,7 +150,16 @@ def main():
     trng = mi.rng_for(args.seed, 77)
     tables_b_np = mi.scatter_page_tables(trng, w.num_pages, w.n)
     tables_b = [up(t) for t in tables_b_np]
-    send = [torch.empty(2 * int(w.n[s]) * Hkv * D, dtype=torch.int16, device=dev) for s in range(B)]
+    # one transfer buffer for the batch: sequence s at byte offset send_off[s]
+    send_elems = [2 * int(w.n[s]) * Hkv * D for s in range(B)]
+    send_off_np = np.concatenate([[0], np.cumsum(send_elems)[:-1]]).astype(np.int64) * 2
+    send_all = torch.empty(int(sum(send_elems)), dtype=torch.int16, device=dev)
+    send = [send_all[int(o) // 2: int(o) // 2 + e] for o, e in zip(send_off_np, send_elems)]
+    send_off = torch.from_numpy(send_off_np).to(dev)
+    r_s0 = up(np.zeros(B, dtype=np.int32))
+    r_s1 = up(w.n.astype(np.int32))
+    table_b, cu_pages_b = up(np.concatenate(tables_b_np).astype(np.int32)), cu_pages
+    max_range_pages = int(max(-(-int(x) // 16) for x in w.n))
     # the cached prefixes [0, b) are already in the cache when a step starts
     wp = w.with_ranges(np.zeros_like(w.b), w.b)
     if int(wp.cu_q[-1]):
@@ -185,11 +194,11 @@ def main():
         if record:
             e1.record()
             attn_events.append((e0, e1))
-        # a4 + a5: ship every sequence's KV [0, n) to the second pool
-        for s in range(B):
-            n = int(w.n[s])
-            mc.mc_kv_pack_range(desc_a, 0, 1, tables_a[s], len(w.page_tables[s]), 0, n, send[s])
-            mc.mc_kv_unpack_range(desc_b, 0, 1, tables_b[s], len(tables_b_np[s]), 0, n, send[s])
+        # a4 + a5: ship every sequence's KV [0, n) to the second pool (one launch each way)
+        mc.mc_kv_pack_batch(desc_a, 0, 1, B, table, cu_pages, r_s0, r_s1, send_off,
+                            max_range_pages, send_all)
+        mc.mc_kv_unpack_batch(desc_b, 0, 1, B, table_b, cu_pages_b, r_s0, r_s1, send_off,
+                              max_range_pages, send_all)
 
     for _ in range(args.warmup):
         step(False)
@@ -235,10 +244,15 @@ def main():
                                   send[s])
     copy["pack_GBps"] = round(2 * kv_bytes / timed(pack_all) / 1e6, 1)
     copy["unpack_GBps"] = round(2 * kv_bytes / timed(unpack_all) / 1e6, 1)
+    copy["pack_batch_GBps"] = round(2 * kv_bytes / timed(lambda: mc.mc_kv_pack_batch(
+        desc_a, 0, 1, B, table, cu_pages, r_s0, r_s1, send_off, max_range_pages, send_all)) / 1e6, 1)
+    copy["unpack_batch_GBps"] = round(2 * kv_bytes / timed(lambda: mc.mc_kv_unpack_batch(
+        desc_b, 0, 1, B, table_b, cu_pages_b, r_s0, r_s1, send_off, max_range_pages,
+        send_all)) / 1e6, 1)
     copy["payload_MiB"] = round(kv_bytes / 2**20, 1)
     if not args.no_copy_sweep:
         # 32768 tokens x 32 layers = 4 GiB of KV between two pools (long-context transfer)
-        del pool_a, pool_b, send
+        del pool_a, pool_b, send, send_all
         torch.cuda.empty_cache()
         L, T = 32, 32768
         npg = T // 16
@@ -305,7 +319,7 @@ def main():
                    "seed": args.seed, "total_new_tokens": total_q,
                    "total_tokens": int(np.sum(w.n)),
                    "useful_attention_flops_per_step": flops,
-                   "step": "alloc + append + plan + attention + pack + unpack"},
+                   "step": "alloc + append + plan + attention + pack_batch + unpack_batch"},
         "roofline": {"kernel": "attn_kernel<bf16, G=4>", "bound": "mfma",
                      "achieved": round(attn_tflops, 2), "peak": MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / MFMA_PEAK_TFLOPS, 4),

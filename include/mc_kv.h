@@ -181,6 +181,33 @@ mc_status mc_kv_unpack_range(const mc_pool_desc* pool, int32_t layer_begin, int3
                              const int32_t* pages /* device */, int32_t n_table_pages, int32_t s0,
                              int32_t s1, const void* sendbuf /* device */, void* stream);
 
+/* Batched form of the two calls above: one launch moves the ranges of `batch` sequences (an
+ * engine serves several remote_send requests per layer, Sec. 3.5).  Sequence s owns table
+ * entries [cu_pages[s], cu_pages[s+1]) of page_table, tokens [s0[s], s1[s]) and the buffer
+ * slice starting buf_offset[s] bytes into sendbuf (a multiple of 16; layout
+ * [layer - layer_begin][2][token - s0[s]][kv_head][D] as above; slices must not overlap).
+ * All five arrays are device memory; buf_offset is int64.  max_range_pages (host) is the
+ * largest number of table entries any range touches, (s1-1)/16 - s0/16 + 1; it sizes the
+ * launch, pages beyond it are not moved.  A sequence whose entries are malformed (empty or
+ * reversed range, negative or misaligned offset, table too short, page id outside the pool)
+ * is skipped in whole or in part, never read or written out of bounds.  The result for each
+ * sequence equals that of the single-sequence call. */
+mc_status mc_kv_pack_batch(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                           int32_t batch, const int32_t* page_table /* device */,
+                           const int32_t* cu_pages /* device [batch+1] */,
+                           const int32_t* s0 /* device [batch] */,
+                           const int32_t* s1 /* device [batch] */,
+                           const int64_t* buf_offset /* device [batch] */,
+                           int32_t max_range_pages, void* sendbuf /* device */, void* stream);
+mc_status mc_kv_unpack_batch(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                             int32_t batch, const int32_t* page_table /* device */,
+                             const int32_t* cu_pages /* device [batch+1] */,
+                             const int32_t* s0 /* device [batch] */,
+                             const int32_t* s1 /* device [batch] */,
+                             const int64_t* buf_offset /* device [batch] */,
+                             int32_t max_range_pages, const void* sendbuf /* device */,
+                             void* stream);
+
 #ifdef __cplusplus
 }
 #endif

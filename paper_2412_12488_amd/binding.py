@@ -18,6 +18,7 @@ EXPORTS = [
     "mc_kv_allocator_num_free", "mc_kv_check_page_table",
     "mc_kv_append", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_check",
     "mc_prefix_prefill_attn", "mc_kv_pack_range", "mc_kv_unpack_range",
+    "mc_kv_pack_batch", "mc_kv_unpack_batch",
 ]
 
 
@@ -65,6 +66,8 @@ def lib():
                                          vp, vp, vp, sz, vp]
     L.mc_kv_pack_range.argtypes = [pd, i32, i32, vp, i32, i32, i32, vp, vp]
     L.mc_kv_unpack_range.argtypes = [pd, i32, i32, vp, i32, i32, i32, vp, vp]
+    L.mc_kv_pack_batch.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
+    L.mc_kv_unpack_batch.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
     _lib = L
     return L
 
@@ -189,3 +192,19 @@ def mc_kv_unpack_range(pool: mc_pool_desc, layer_begin, layer_end, pages, n_tabl
     _check(lib().mc_kv_unpack_range(C.byref(pool), layer_begin, layer_end, _ptr(pages),
                                     n_table_pages, s0, s1, _ptr(sendbuf), _stream(stream)),
            "mc_kv_unpack_range")
+
+
+def mc_kv_pack_batch(pool: mc_pool_desc, layer_begin, layer_end, batch, page_table, cu_pages, s0,
+                     s1, buf_offset, max_range_pages, sendbuf, stream=None):
+    _check(lib().mc_kv_pack_batch(C.byref(pool), layer_begin, layer_end, batch, _ptr(page_table),
+                                  _ptr(cu_pages), _ptr(s0), _ptr(s1), _ptr(buf_offset),
+                                  max_range_pages, _ptr(sendbuf), _stream(stream)),
+           "mc_kv_pack_batch")
+
+
+def mc_kv_unpack_batch(pool: mc_pool_desc, layer_begin, layer_end, batch, page_table, cu_pages,
+                       s0, s1, buf_offset, max_range_pages, sendbuf, stream=None):
+    _check(lib().mc_kv_unpack_batch(C.byref(pool), layer_begin, layer_end, batch,
+                                    _ptr(page_table), _ptr(cu_pages), _ptr(s0), _ptr(s1),
+                                    _ptr(buf_offset), max_range_pages, _ptr(sendbuf),
+                                    _stream(stream)), "mc_kv_unpack_batch")

@@ -32,11 +32,29 @@ struct RangeArgs {
   int32_t layer_begin;
   int32_t s0, s1;
   int32_t hkv;
+  // batched form only (blockIdx.z = sequence): per-sequence ranges, tables and buffer offsets
+  const int32_t* cu_pages;
+  const int32_t* s0_of;
+  const int32_t* s1_of;
+  const int64_t* buf_offset;
 };
 
 // grid.x: page index within [s0/16, ceil(s1/16)); grid.y: (layer - layer_begin)*2 + kv
-template <bool kPack>
+template <bool kPack, bool kBatched>
 __global__ __launch_bounds__(kThreads) void range_copy_kernel(RangeArgs a) {
+  if (kBatched) {
+    // this sequence's table, range and slice of the buffer; malformed entries are skipped
+    const int sq = blockIdx.z;
+    const int p0 = a.cu_pages[sq], p1 = a.cu_pages[sq + 1];
+    a.s0 = a.s0_of[sq];
+    a.s1 = a.s1_of[sq];
+    const int64_t off = a.buf_offset[sq];
+    if (p0 < 0 || p1 < p0 || a.s0 < 0 || a.s1 <= a.s0 || off < 0 || (off & 15)) return;
+    a.pages += p0;
+    a.n_table_pages = p1 - p0;
+    a.buf += off;
+    if (a.s0 / kPage + (int)blockIdx.x > (a.s1 - 1) / kPage) return;
+  }
   const int tp = a.s0 / kPage + blockIdx.x;          // table index
   const int lk = blockIdx.y;
   const int slot = threadIdx.x >> 4, lane16 = threadIdx.x & 15;
@@ -151,13 +169,58 @@ mc_status range_copy(bool pack, const mc_pool_desc* pool, int32_t layer_begin, i
   a.s0 = s0;
   a.s1 = s1;
   a.hkv = pool->num_kv_heads;
+  a.cu_pages = nullptr;
+  a.s0_of = nullptr;
+  a.s1_of = nullptr;
+  a.buf_offset = nullptr;
   const int first = s0 / kPage, last = (s1 - 1) / kPage;
   dim3 grid(last - first + 1, (unsigned)gy);
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (pack)
-    hipLaunchKernelGGL(range_copy_kernel<true>, grid, dim3(kThreads), 0, hs, a);
+    hipLaunchKernelGGL((range_copy_kernel<true, false>), grid, dim3(kThreads), 0, hs, a);
   else
-    hipLaunchKernelGGL(range_copy_kernel<false>, grid, dim3(kThreads), 0, hs, a);
+    hipLaunchKernelGGL((range_copy_kernel<false, false>), grid, dim3(kThreads), 0, hs, a);
+  return mc::launch_status();
+}
+
+mc_status range_copy_batch(bool pack, const mc_pool_desc* pool, int32_t layer_begin,
+                           int32_t layer_end, int32_t batch, const int32_t* page_table,
+                           const int32_t* cu_pages, const int32_t* s0, const int32_t* s1,
+                           const int64_t* buf_offset, int32_t max_range_pages, void* sendbuf,
+                           void* stream) {
+  mc_status st = mc::check_pool(pool);
+  if (st != MC_OK) return st;
+  if (layer_begin < 0 || layer_end < layer_begin || layer_end > pool->num_layers)
+    return MC_ERR_RANGE;
+  if (batch < 0 || max_range_pages < 0) return MC_ERR_INVALID;
+  if (batch == 0 || max_range_pages == 0 || layer_begin == layer_end) return MC_OK;
+  if (!page_table || !cu_pages || !s0 || !s1 || !buf_offset || !sendbuf ||
+      !mc::aligned16(sendbuf) || (reinterpret_cast<uintptr_t>(buf_offset) & 7u))
+    return MC_ERR_INVALID;
+  const int64_t gy = 2ll * (layer_end - layer_begin);
+  if (gy > 65535 || batch > 65535) return MC_ERR_UNSUPPORTED;
+  RangeArgs a;
+  a.pool = static_cast<char*>(pool->base);
+  a.buf = static_cast<char*>(sendbuf);
+  a.pages = page_table;
+  a.layer_stride = mc::layer_stride_bytes(pool);
+  a.page_stride = mc::page_stride_bytes(pool);
+  a.num_pages = pool->num_pages;
+  a.n_table_pages = 0;
+  a.layer_begin = layer_begin;
+  a.s0 = 0;
+  a.s1 = 0;
+  a.hkv = pool->num_kv_heads;
+  a.cu_pages = cu_pages;
+  a.s0_of = s0;
+  a.s1_of = s1;
+  a.buf_offset = buf_offset;
+  dim3 grid((unsigned)max_range_pages, (unsigned)gy, (unsigned)batch);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (pack)
+    hipLaunchKernelGGL((range_copy_kernel<true, true>), grid, dim3(kThreads), 0, hs, a);
+  else
+    hipLaunchKernelGGL((range_copy_kernel<false, true>), grid, dim3(kThreads), 0, hs, a);
   return mc::launch_status();
 }
 
@@ -177,6 +240,22 @@ mc_status mc_kv_unpack_range(const mc_pool_desc* pool, int32_t layer_begin, int3
                              const void* sendbuf, void* stream) {
   return range_copy(false, pool, layer_begin, layer_end, pages, n_table_pages, s0, s1,
                     const_cast<void*>(sendbuf), stream);
+}
+
+mc_status mc_kv_pack_batch(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                           int32_t batch, const int32_t* page_table, const int32_t* cu_pages,
+                           const int32_t* s0, const int32_t* s1, const int64_t* buf_offset,
+                           int32_t max_range_pages, void* sendbuf, void* stream) {
+  return range_copy_batch(true, pool, layer_begin, layer_end, batch, page_table, cu_pages, s0, s1,
+                          buf_offset, max_range_pages, sendbuf, stream);
+}
+
+mc_status mc_kv_unpack_batch(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                             int32_t batch, const int32_t* page_table, const int32_t* cu_pages,
+                             const int32_t* s0, const int32_t* s1, const int64_t* buf_offset,
+                             int32_t max_range_pages, const void* sendbuf, void* stream) {
+  return range_copy_batch(false, pool, layer_begin, layer_end, batch, page_table, cu_pages, s0, s1,
+                          buf_offset, max_range_pages, const_cast<void*>(sendbuf), stream);
 }
 
 mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer, const void* k_new,

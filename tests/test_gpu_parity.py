@@ -99,6 +99,64 @@ def test_pack_unpack_bytes(s0, s1, Hkv):
     assert np.array_equal(bits(pool_b.t), opool_b)
 
 
+def test_pack_unpack_batch_bytes():
+    """One launch for several sequences gives, for each, the bytes of the single-sequence call."""
+    L, Hkv = 3, 8
+    lens = [300, 16, 77, 1, 130]
+    s0 = [0, 3, 16, 0, 129]
+    s1 = [300, 16, 70, 1, 130]
+    w = small_workload(105, mi.BF16, Hkv, Hkv, lens, [0] * 5, layers=L)
+    init = canary(8, DevPool(w).elems)
+    pool_a = DevPool(w, fill=init)
+    B = len(lens)
+    sizes = [(L - 1) * 2 * (s1[i] - s0[i]) * Hkv * 128 for i in range(B)]     # elements
+    guard = 64
+    offs, at = [], guard
+    for n in sizes:
+        offs.append(at)
+        at += n + guard                      # guard elements between and around the slices
+    raw = canary(9, at)
+    send = dev(raw)
+    db = DevBatch(w)
+    d_s0, d_s1 = dev(np.array(s0, np.int32)), dev(np.array(s1, np.int32))
+    d_off = torch.tensor([2 * o for o in offs], dtype=torch.int64, device=DEV)   # bytes
+    max_pages = max((b - 1) // 16 - a // 16 + 1 for a, b in zip(s0, s1))
+    mc.mc_kv_pack_batch(pool_a.desc, 1, L, B, db.page_table, db.cu_pages, d_s0, d_s1, d_off,
+                        max_pages, send)
+    torch.cuda.synchronize()
+    got = bits(send)
+    expect = raw.copy()
+    refs = []
+    for i in range(B):
+        ref = oracle.pack(init, pool_a.shape, 1, L, w.page_tables[i], s0[i], s1[i])
+        refs.append(ref)
+        expect[offs[i]:offs[i] + sizes[i]] = ref.ravel()
+    assert np.array_equal(got, expect)                  # slices and every guard byte
+    assert np.array_equal(bits(pool_a.t), init)
+    # receiver: other tables, same launch shape
+    init_b = canary(10, pool_a.elems)
+    pool_b = DevPool(w, fill=init_b)
+    tables_b = mi.scatter_page_tables(mi.rng_for(11), w.num_pages, w.n)
+    wb = mi.Workload("b", w.seed, w.dtype, L, Hkv, Hkv, w.num_pages, w.n, w.b, tables_b)
+    dbb = DevBatch(wb)
+    mc.mc_kv_unpack_batch(pool_b.desc, 1, L, B, dbb.page_table, dbb.cu_pages, d_s0, d_s1, d_off,
+                          max_pages, send)
+    torch.cuda.synchronize()
+    opool_b = init_b.copy()
+    for i in range(B):
+        oracle.unpack(opool_b, pool_a.shape, 1, L, tables_b[i], s0[i], s1[i], refs[i])
+    assert np.array_equal(bits(pool_b.t), opool_b)
+    # a malformed sequence (reversed range) is skipped, the others still move
+    send2 = dev(raw)
+    bad_s1 = dev(np.array([300, 2, 70, 1, 130], np.int32))      # sequence 1: s1 < s0
+    mc.mc_kv_pack_batch(pool_a.desc, 1, L, B, db.page_table, db.cu_pages, d_s0, bad_s1, d_off,
+                        max_pages, send2)
+    torch.cuda.synchronize()
+    expect2 = expect.copy()
+    expect2[offs[1]:offs[1] + sizes[1]] = raw[offs[1]:offs[1] + sizes[1]]
+    assert np.array_equal(bits(send2), expect2)
+
+
 def test_transfer_then_attend_equals_local_attention():
     """KV sent to a second pool is attended there exactly as at home (Sec. 3.4)."""
     w = small_workload(104, mi.BF16, 32, 8, [200], [150], num_pages=40)

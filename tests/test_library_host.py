@@ -119,6 +119,14 @@ def test_validation_rejects_before_launch():
     # empty ranges are fine and launch nothing
     assert _status(pk, ok, 0, 1, FAKE, 4, 5, 5, FAKE) == mc.MC_OK
     assert _status(mc.mc_kv_unpack_range, ok, 1, 1, FAKE, 4, 0, 16, FAKE) == mc.MC_OK
+    pb = mc.mc_kv_pack_batch
+    assert _status(pb, ok, 0, 3, 2, FAKE, FAKE, FAKE, FAKE, FAKE, 4, FAKE) == mc.MC_ERR_RANGE
+    assert _status(pb, ok, 0, 1, -1, FAKE, FAKE, FAKE, FAKE, FAKE, 4, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pb, ok, 0, 1, 2, FAKE, FAKE, None, FAKE, FAKE, 4, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pb, ok, 0, 1, 2, FAKE, FAKE, FAKE, FAKE, FAKE + 4, 4, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pb, ok, 0, 1, 2, FAKE, FAKE, FAKE, FAKE, FAKE, 4, FAKE + 8) == mc.MC_ERR_INVALID
+    assert _status(pb, ok, 0, 1, 0, FAKE, FAKE, FAKE, FAKE, FAKE, 4, FAKE) == mc.MC_OK
+    assert _status(mc.mc_kv_unpack_batch, ok, 0, 1, 2, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE) == mc.MC_OK
     ap = mc.mc_kv_append
     assert _status(ap, ok, 2, FAKE, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE) == mc.MC_ERR_RANGE
     assert _status(ap, ok, 0, None, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE) == mc.MC_ERR_INVALID
