@@ -294,18 +294,26 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
-// Pipeline of one workgroup (one barrier per KV tile):
-//   iteration j   issues the global->LDS copies of K(j+2) and V(j+1)   (asynchronous, no VGPRs)
-//                 finds the row max of S(j), rescales O only if the max moved far
-//                 computes S(j+1) = K(j+1) Q^T on the MFMA pipe while the VALU does the
-//                 exponentials of S(j), then O^T += V(j)^T P(j)^T
-//   so K is always one tile ahead of V, and two LDS buffers of each are enough.
+// Pipeline of one workgroup.  A KV tile (64 keys, 4 pages) is the unit of the V staging
+// and of the workgroup barrier; a half tile (32 keys, 2 pages) is the unit of the K staging and
+// of the softmax pipeline.  Half tile h lives in slot h % 4 of a ring of four K buffers, V
+// tile j in V buffer j % 2.
+//   tile j        issues the global->LDS copies of V(j+1) and of K halves 2j+3, 2j+4
+//                 (asynchronous, no VGPRs), runs half steps 2j and 2j+1, waits for the copies
+//   half step h   phase 1: S(h+1) = K(h+1) Q^T on the MFMA pipe, exponentials of S(h) on the VALU
+//                 phase 2: O^T += V(h)^T P(h)^T on the MFMA pipe, row max of S(h+1) on the VALU
+//                 O is rescaled only if a row max moved far
+// The two score register sets swap roles every half step, so a tile starts and ends with the
+// same set and nothing is copied.  Each step of a phase is one MFMA, at most one LDS fragment
+// fetch (4 MFMAs ahead of its use) and a slice of the VALU work; the order is pinned.
 template <typename T, int G>
 __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   constexpr int TOK = kBM / G;  // tokens per q tile
+  constexpr int kHalf = kBN / 2;
+  constexpr int kHalfBytes = kTileBytes / 2;
   typedef typename Mfma<T>::vec8 vec8;
-  __shared__ __attribute__((aligned(1024))) char lds_k[2 * kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char lds_v[2 * kTileBytes];
+  // 4 K half tiles then 2 V tiles; reused as the output staging area at the end
+  __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];
 
   const int hk = blockIdx.x % a.hkv;
   const int wi = blockIdx.x / a.hkv;
@@ -324,6 +332,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const int first_pos = b + row0;                    // position of the tile's first token
   const int kv_len = first_pos + ntok;               // keys [0, kv_len) are needed
   const int n_kv_tiles = (kv_len + kBN - 1) / kBN;
+  const int n_halves = (kv_len + kHalf - 1) / kHalf;
+  // half h is fully visible to every row of the q tile iff 32 (h+1) <= first_pos + 1
+  const int n_full = (first_pos + 1) / kHalf;
   const int last_pidx = (kv_len - 1) / kPage;        // last table entry that holds a needed key
   const_i32_ptr table = (const_i32_ptr)(a.page_table + a.cu_pages[seq]);
 
@@ -345,65 +356,81 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 
   // ---- global -> LDS copies (no VGPR staging) -------------------------------------
   // A wavefront's copy instruction fills 1 KiB of LDS linearly (lane L -> bytes 16 L..),
-  // i.e. 4 tile rows.  Copy i of wave w fills rows 16 i + 4 w + L/16 (page i of the tile,
-  // slots 4 w..4 w+3); lane L fetches the 16-byte chunk that the swizzle wants at position
-  // L%16 of that row.  Rows of keys at or beyond kv_len receive whatever the page holds
-  // (K: discarded by the mask; V: zeroed in LDS before the last tile's P.V, since 0 x NaN
-  // would poison the accumulators).
+  // i.e. 4 rows.  A page is 16 rows: wave w fills rows 4 w + L/16 of the page (slots
+  // 4 w..4 w+3); lane L fetches the 16-byte chunk that the swizzle wants at position L%16 of
+  // that row.  Rows of keys at or beyond kv_len receive whatever the page holds (K: discarded
+  // by the mask; V: zeroed in LDS before the last tile's P.V, since 0 x NaN would poison the
+  // accumulators).
   const int ld_slot = 4 * wave + (lane >> 4), ld_pos = lane & 15;
   const char* pool_k = a.pool_layer + (int64_t)hk * kHeadPageBytes;
   const uint32_t k_lane_off = ld_slot * kRowBytes + ((ld_pos ^ ld_slot) << 4);
   const uint32_t v_lane_off = ld_slot * kRowBytes + ((ld_pos ^ ((ld_slot & 3) << 2)) << 4) +
                               (uint32_t)a.hkv * kHeadPageBytes;   // V run sits hkv blocks after K
   const uint32_t page_blocks = 2u * a.hkv;     // 4 KiB blocks per page
-  // wave-uniform address of this kv head's K run in each of the 4 pages of tile jt.  Table
-  // entries past the last needed one are replaced by the last needed one.
-  struct TilePages { const char* base[4]; };
-  auto page_base = [&](int32_t pg) {
+  const uint32_t lds_k = lds_addr(lds), lds_v = lds_k + 2 * kTileBytes;
+  // wave-uniform address of this kv head's K run in the page of table entry pidx; entries
+  // past the last needed one are replaced by the last needed one
+  auto page_base = [&](int32_t pg) __attribute__((always_inline)) {
     pg = min(max(pg, 0), a.num_pages - 1);         // checked by the plan; stay in bounds anyway
     return pool_k + ((uint64_t)((uint32_t)pg * page_blocks) << 12);
   };
-  auto tile_pages = [&](int jt) {                  // scalar reads: used before the loop only
-    TilePages t;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) t.base[i] = page_base(table[min(jt * 4 + i, last_pidx)]);
-    return t;
+  auto copy_page = [&](const char* base, bool is_v, uint32_t lds_page) __attribute__((always_inline)) {   // 16 rows = 4 KiB
+    copy16_to_lds(base, is_v ? v_lane_off : k_lane_off, lds_page + wave * 1024);
   };
-  // Inside the loop the 4 page ids of a tile are fetched one iteration early by a vector
-  // load (lane i & 3 holds id i) and moved to scalar registers when the addresses are built,
-  // so no iteration waits on a page-table read.
+  // The page ids of a tile's copies are fetched one tile early by a vector load (lane i & 7
+  // holds table entry first + i) issued, like the copies, outside the compiler's wait
+  // tracking, and moved to scalar registers when the addresses are built.
   const int32_t* table_g = a.page_table + a.cu_pages[seq];
-  auto fetch_ids = [&](int jt) { return table_g[min(jt * 4 + (lane & 3), last_pidx)]; };
-  auto pages_from_ids = [&](int32_t ids) {
-    TilePages t;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) t.base[i] = page_base(__builtin_amdgcn_readlane(ids, i));
-    return t;
+  auto fetch_ids = [&](int first) __attribute__((always_inline)) {
+    const int32_t* p = table_g + min(first + (lane & 7), last_pidx);
+    int32_t v;
+    asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
   };
-  auto issue_tile = [&](const TilePages& t, bool is_v, char* lds_tile) {
-    const uint32_t dst = lds_addr(lds_tile) + wave * 1024;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      copy16_to_lds(t.base[i], is_v ? v_lane_off : k_lane_off, dst + i * 4096);
-  };
-  auto wait_copies_and_sync = [&]() {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // The wait names ids_next as an operand: the register is written by a load the compiler does
+  // not track, so every later read of it must be ordered after this wait by data dependence.
+  int32_t ids_next;                       // table entries 4j+4 .. 4j+11 during tile j
+  auto wait_copies_and_sync = [&]() __attribute__((always_inline)) {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(ids_next) : : "memory");
     __syncthreads();
   };
 
-  // ---- S^T = K Q^T for one tile: two 32-key chunks ----------------------------------
-  auto qk_tile = [&](const char* ktile, f32x16 (&s_acc)[2]) {
+  // ---- LDS fragment fetches ----------------------------------------------------------
+  // K fragment f (0..7) of a half tile = d-step kk: rows l32, 16-byte chunk 2 kk + half.
+  // V fragment g (0..7) of a half tile (rows crow..crow+31 of its tile): 16-key step st = g >> 2,
+  // d chunk dc = g & 3; a 16-lane group reads 4 keys x 16 d, lane j supplies key (j/4) and d-quad
+  // (j%4); the two reads cover accumulator registers 8 st..8 st+7, i.e. for this lane-half the
+  // keys 16 st + {0..3} + 4 half and 16 st + 8 + {0..3} + 4 half.
+  const int j16 = lane & 15, gq = (lane >> 4) & 1;
+  auto k_frag = [&](uint32_t khalf, int f) __attribute__((always_inline)) {
+    return *reinterpret_cast<const vec8 __attribute__((address_space(3)))*>(
+        (size_t)(khalf + k_swz(l32, 2 * f + half)));
+  };
+  auto v_frag = [&](uint32_t vtile, int crow, int gi) __attribute__((always_inline)) {
+    const int st = gi >> 2, dc = gi & 3;
+    const int key_lo = crow + st * 16 + 4 * half + (j16 >> 2);
+    const int chunk = dc * 4 + gq * 2 + ((j16 & 3) >> 1);
+    const int sub = (j16 & 1) * 8;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4_ptr)(size_t)(vtile + v_swz(key_lo, chunk) + sub));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4_ptr)(size_t)(vtile + v_swz(key_lo + 8, chunk) + sub));
+    return __builtin_bit_cast(vec8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+
+  // key held by accumulator register i of half h: 32 h + 8 (i/4) + 4 half + i%4
+  auto mask_half = [&](int h, f32x16& sc) __attribute__((always_inline)) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s_acc[c][i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const int row = c * 32 + l32;
-        vec8 kfrag = *reinterpret_cast<const vec8*>(ktile + k_swz(row, 2 * kk + half));
-        s_acc[c] = Mfma<T>::run(kfrag, qreg[kk], s_acc[c]);
-      }
+    for (int i = 0; i < 16; ++i) {
+      const int key = h * kHalf + 8 * (i >> 2) + 4 * half + (i & 3);
+      if (key > my_pos) sc[i] = -INFINITY;
     }
+  };
+  // the other 16 keys of the row's half tile sit in lane l ^ 32: swap the wave's halves on the VALU
+  auto max_across_halves = [&](float mx) __attribute__((always_inline)) {
+    const uint32_t bits = __builtin_bit_cast(uint32_t, mx);
+    const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+    return fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
   };
 
   f32x16 o_acc[4];
@@ -412,106 +439,48 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) o_acc[dc][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;   // reference max (raw scores), this lane's partial sum
+  float mx_cur;                           // row max of the half tile about to be exponentiated
   const float c2 = a.scale_log2;
-  // per-lane constants of the transposing V read: 16-lane group gq, lane j in group
-  const int j16 = lane & 15, gq = (lane >> 4) & 1;
+  const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  constexpr int kAhead = 4;               // fragments in flight
+  vec8 kf[kAhead];                        // first K fragments of the next phase 1
 
-  // key held by accumulator register i of chunk c of tile jt: 64 jt + 32 c + 8 (i/4) + 4 half + i%4
-  auto mask_tile = [&](int jt, f32x16 (&s)[2]) {
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = jt * kBN + c * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-        if (key > my_pos) s[c][i] = -INFINITY;
-      }
-  };
-  auto row_max = [&](const f32x16 (&s)[2]) {
-    float mx = s[0][0];
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) mx = max3(mx, s[c][i], s[c][i + 1]);
-    // the other 32 keys of the row sit in lane l ^ 32: swap the wave's halves on the VALU
-    const uint32_t bits = __builtin_bit_cast(uint32_t, mx);
-    const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
-    return fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
-  };
-
-  // tile j is fully visible to every row of the q tile iff 64 (j+1) <= first_pos + 1
-  const int n_full = (first_pos + 1) / kBN;
-
-  f32x16 s_cur[2];
-  TilePages pages_next = tile_pages(min(1, n_kv_tiles - 1));   // pages of tile j+1 during tile j
-  int32_t ids_next2 = fetch_ids(min(2, n_kv_tiles - 1));       // ids of tile j+2 during tile j
+  // ---- prologue: K halves 0, 1, 2 and V(0) in flight together; S(half 0) -------------
+  f32x16 s_a, s_b;
   {
-    const TilePages p0 = tile_pages(0);
-    issue_tile(p0, false, lds_k);
-    issue_tile(p0, true, lds_v);
-    issue_tile(pages_next, false, lds_k + kTileBytes);
+    // table entries 0..5 (K halves 0..2), 0..3 (V tile 0)
+    const char* pb[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) pb[i] = page_base(table[min(i, last_pidx)]);
+#pragma unroll
+    for (int i = 0; i < 6; ++i) copy_page(pb[i], false, lds_k + i * 4096);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) copy_page(pb[i], true, lds_v + i * 4096);
   }
+  ids_next = fetch_ids(4);
   wait_copies_and_sync();
-  qk_tile(lds_k, s_cur);
-  if (n_full == 0) mask_tile(0, s_cur);
-  float mx_cur = row_max(s_cur);
-  __syncthreads();   // every wave has read K(0) before the first iteration overwrites it
+#pragma unroll
+  for (int f = 0; f < 8; ++f) s_a = Mfma<T>::run(k_frag(lds_k, f), qreg[f], f == 0 ? zero16 : s_a);
+  if (n_full == 0) mask_half(0, s_a);
+  {
+    float mx = s_a[0];
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) mx = max3(mx, s_a[i], s_a[i + 1]);
+    mx_cur = max_across_halves(mx);
+  }
+  __syncthreads();   // every wave has read K half 0 before tile 0 overwrites its slot
 
-  // One KV tile.  HAS_NEXT: tile j+1 exists; MASK_NEXT: it reaches the causal diagonal.
-  auto body = [&](int jt, auto mask_tag, auto next_tag) {
-    constexpr bool MASK_NEXT = decltype(mask_tag)::value;
-    constexpr bool HAS_NEXT = decltype(next_tag)::value;
-    const int par = jt & 1;
-    const char* ktile = lds_k + (par ^ 1) * kTileBytes;   // K(j+1)
-    const char* vtile = lds_v + par * kTileBytes;         // V(j)
-    // Operand fragments are fetched from LDS a fixed number of MFMAs ahead of their use.
-    // QK step t (0..15): key chunk c = t & 1, d-step kk = t >> 1 (the two accumulator chains
-    // alternate).  PV step u (0..15): key chunk c = u >> 3, 16-key step s = (u >> 2) & 1,
-    // d chunk dc = u & 3 (four accumulator chains alternate); the step covers accumulator
-    // registers 8s..8s+7 of chunk c, i.e. for this lane-half the keys
-    // 32c + 16s + {0..3} + 4 half and 32c + 16s + 8 + {0..3} + 4 half.
-    constexpr int kAhead = 4;
-    auto k_frag = [&](int t) {
-      return *reinterpret_cast<const vec8*>(ktile + k_swz((t & 1) * 32 + l32, 2 * (t >> 1) + half));
-    };
-    auto v_frag = [&](int u) {
-      const int c = u >> 3, st = (u >> 2) & 1, dc = u & 3;
-      // 16-lane group reads 4 keys x 16 d; lane j supplies key (j/4), d-quad (j%4)
-      const int key_lo = c * 32 + st * 16 + 4 * half + (j16 >> 2);
-      const int chunk = dc * 4 + gq * 2 + ((j16 & 3) >> 1);
-      const int sub = (j16 & 1) * 8;
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (lds_s16x4_ptr)(vtile + v_swz(key_lo, chunk) + sub));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (lds_s16x4_ptr)(vtile + v_swz(key_lo + 8, chunk) + sub));
-      return __builtin_bit_cast(vec8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-    };
-    vec8 kf[kAhead], vf[kAhead];
-    if (HAS_NEXT) {
-#pragma unroll
-      for (int t = 0; t < kAhead; ++t) kf[t] = k_frag(t);
-      const TilePages pages_next2 = pages_from_ids(ids_next2);
-      issue_tile(pages_next2, false, lds_k + par * kTileBytes);
-      issue_tile(pages_next, true, lds_v + (par ^ 1) * kTileBytes);
-      pages_next = pages_next2;
-      ids_next2 = fetch_ids(min(jt + 3, n_kv_tiles - 1));
-    } else {
-      if (kv_len < (jt + 1) * kBN) {
-        // last tile: zero the V rows of keys >= kv_len (their P is 0, their bytes are arbitrary)
-        const int valid = kv_len - jt * kBN;
-        const u32x4 zero = {0, 0, 0, 0};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = i * 16 + (tid >> 4);
-          if (row >= valid)
-            *reinterpret_cast<u32x4*>(lds_v + par * kTileBytes + row * kRowBytes + (tid & 15) * 16) = zero;
-        }
-        __syncthreads();
-      }
-#pragma unroll
-      for (int u = 0; u < kAhead; ++u) vf[u] = v_frag(u);
-    }
-    // ---- move the reference max (and rescale O, l) only when some row's max rose by
-    //      more than 2^8 in the exp2 domain: p stays below 2^8, sums stay exact
+  // ---- one half step.  s_cur = S(h) in, s_next = S(h+1) out (computed even when half h+1
+  //      does not exist: its LDS rows are then stale, the result is never used).
+  //      k_next: LDS address of K half h+1; k_after: of K half h+2, whose first fragments are
+  //      fetched at the end of this step if fetch_after; v_cur/crow: V tile and row offset of
+  //      half h.  mask_next: half h+1 reaches the causal diagonal.
+  auto half_step = [&](int h, uint32_t k_next, bool fetch_after, uint32_t k_after, uint32_t v_cur,
+                       int crow, f32x16& s_cur, f32x16& s_next,
+                       bool mask_next) __attribute__((always_inline)) {
+    vec8 vf[kAhead];
+    // ---- move the reference max (and rescale O, l) only when some row's max rose by more
+    //      than 2^8 in the exp2 domain: p stays below 2^8, sums stay exact
     if (__builtin_amdgcn_ballot_w64((mx_cur - m_run) * c2 > 8.f) != 0) {
       const float m_new = fmaxf(m_run, mx_cur);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
@@ -523,62 +492,100 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
         for (int i = 0; i < 16; ++i) o_acc[dc][i] *= alpha;
     }
     const float mc2 = m_run * c2;
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- phase 1: S(j+1) = K(j+1) Q^T on the MFMA pipe, exponentials of S(j) on the VALU.
-    //      Each step: one MFMA, one fragment fetch for kAhead steps later, 1/16 of the softmax.
-    f32x16 s_next[2];
-    const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     float psum = 0.f;
-    uint32_t p_pk[2][8];
+    uint32_t p_pk[8];
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- phase 1: 8 steps.  Step t: d-step t of S(h+1); softmax of register pair t of S(h)
+    //      (registers 2t, 2t+1 -> packed operand word t).
 #pragma unroll
-    for (int t = 0; t < 16; ++t) {
+    for (int t = 0; t < 8; ++t) {
       {
-        const int c = t >> 3, i = 2 * (t & 7);
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[c][i], c2, -mc2));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[c][i + 1], c2, -mc2));
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[2 * t], c2, -mc2));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[2 * t + 1], c2, -mc2));
         psum += p0 + p1;   // the unrounded values: LSE must not inherit P's 2-byte rounding
-        p_pk[c][t & 7] = Mfma<T>::pack2(p0, p1);
+        p_pk[t] = Mfma<T>::pack2(p0, p1);
       }
-      if (HAS_NEXT) {
-        s_next[t & 1] = Mfma<T>::run(kf[t % kAhead], qreg[t >> 1], t < 2 ? zero16 : s_next[t & 1]);
-        if (t + kAhead < 16) kf[t % kAhead] = k_frag(t + kAhead);
-        else vf[(t + kAhead) % kAhead] = v_frag(t + kAhead - 16);
-      }
+      s_next = Mfma<T>::run(kf[t % kAhead], qreg[t], t == 0 ? zero16 : s_next);
+      if (t + kAhead < 8) kf[t % kAhead] = k_frag(k_next, t + kAhead);
+      else vf[t % kAhead] = v_frag(v_cur, crow, t + kAhead - 8);
       __builtin_amdgcn_sched_barrier(0);
     }
     l_run += psum;
-    if (HAS_NEXT && MASK_NEXT) mask_tile(jt + 1, s_next);
-    // ---- phase 2: O^T += V(j)^T P(j)^T on the MFMA pipe, row max of S(j+1) on the VALU ----
+    if (mask_next) mask_half(h + 1, s_next);
+    // ---- phase 2: 8 steps.  Step u: V fragment u (16-key step st = u >> 2 -> operand words
+    //      4 st..4 st+3, d chunk dc = u & 3); row max over register pair u of S(h+1).
     float mx = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int c = u >> 3, st = (u >> 2) & 1, dc = u & 3;
-      u32x4 pw = {p_pk[c][4 * st], p_pk[c][4 * st + 1], p_pk[c][4 * st + 2], p_pk[c][4 * st + 3]};
+    for (int u = 0; u < 8; ++u) {
+      const int st = u >> 2, dc = u & 3;
+      u32x4 pw = {p_pk[4 * st], p_pk[4 * st + 1], p_pk[4 * st + 2], p_pk[4 * st + 3]};
       o_acc[dc] = Mfma<T>::run(vf[u % kAhead], __builtin_bit_cast(vec8, pw), o_acc[dc]);
-      if (u + kAhead < 16) vf[u % kAhead] = v_frag(u + kAhead);
-      if (HAS_NEXT) mx = max3(mx, s_next[u >> 3][2 * (u & 7)], s_next[u >> 3][2 * (u & 7) + 1]);
+      if (u + kAhead < 8) vf[u % kAhead] = v_frag(v_cur, crow, u + kAhead);
+      else if (fetch_after) kf[u % kAhead] = k_frag(k_after, u + kAhead - 8);
+      mx = max3(mx, s_next[2 * u], s_next[2 * u + 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (HAS_NEXT) {
-      // the other 32 keys of the row sit in lane l ^ 32: swap the wave's halves on the VALU
-      const uint32_t bits = __builtin_bit_cast(uint32_t, mx);
-      const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
-      mx_cur = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
-      s_cur[0] = s_next[0];
-      s_cur[1] = s_next[1];
+    mx_cur = max_across_halves(mx);
+  };
+
+  // ---- one tile.  par = j & 1 fixes every LDS address of the tile: K halves 2j+1, 2j+2 are
+  //      read from ring slots 1, 2 (even j) or 3, 0 (odd j) while halves 2j+3, 2j+4 are copied
+  //      into the other two; V(j) is read from V buffer par while V(j+1) is copied into the other.
+  auto tile = [&](int jt, const int par, bool mask0, bool mask1,
+                  bool in_main_loop) __attribute__((always_inline)) {
+    const uint32_t k_h1 = lds_k + (par ? 3 : 1) * kHalfBytes;     // K half 2j+1
+    const uint32_t k_h2 = lds_k + (par ? 0 : 2) * kHalfBytes;     // K half 2j+2
+    const uint32_t k_h3 = lds_k + (par ? 1 : 3) * kHalfBytes;     // K half 2j+3 (copy target)
+    const uint32_t k_h4 = lds_k + (par ? 2 : 0) * kHalfBytes;     // K half 2j+4 (copy target)
+    const uint32_t v_cur = lds_v + par * kTileBytes, v_nxt = lds_v + (par ^ 1) * kTileBytes;
+#pragma unroll
+    for (int f = 0; f < kAhead; ++f) kf[f] = k_frag(k_h1, f);
+    if (in_main_loop || jt + 1 < n_kv_tiles) {
+      // table entries 4j+4 .. 4j+9: V(j+1) is entries +4..+7, K halves 2j+3, 2j+4 are +6..+9
+      const char* pb[6];
+#pragma unroll
+      for (int i = 0; i < 6; ++i) pb[i] = page_base(__builtin_amdgcn_readlane(ids_next, i));
+      ids_next = fetch_ids(4 * jt + 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) copy_page(pb[i], true, v_nxt + i * 4096);
+      copy_page(pb[2], false, k_h3);
+      copy_page(pb[3], false, k_h3 + 4096);
+      copy_page(pb[4], false, k_h4);
+      copy_page(pb[5], false, k_h4 + 4096);
+    } else if (kv_len < (jt + 1) * kBN) {
+      // last tile: zero the V rows of keys >= kv_len (their P is 0, their bytes are arbitrary)
+      const int valid = kv_len - jt * kBN;
+      const u32x4 zero = {0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 16 + (tid >> 4);
+        if (row >= valid)
+          *reinterpret_cast<u32x4 __attribute__((address_space(3)))*>(
+              (size_t)(v_cur + row * kRowBytes + (tid & 15) * 16)) = zero;
+      }
+      __syncthreads();
     }
+    half_step(2 * jt, k_h1, true, k_h2, v_cur, 0, s_a, s_b, mask0);
+    if (in_main_loop || 2 * jt + 1 < n_halves)
+      half_step(2 * jt + 1, k_h2, false, 0, v_cur, kHalf, s_b, s_a, mask1);
     wait_copies_and_sync();
   };
 
+  // Tiles whose two half steps need no mask on their successor halves (2j+1, 2j+2 below the
+  // diagonal) run two per iteration with constant LDS addresses; the rest follow one by one.
+  const int n_main = max(0, min(n_full - 2, 2 * n_kv_tiles - 2) / 2);   // tiles j with 2j+2 < n_full
   int jt = 0;
-  for (; jt < min(n_full, n_kv_tiles) - 1; ++jt) body(jt, std::false_type{}, std::true_type{});
-  for (; jt < n_kv_tiles - 1; ++jt) body(jt, std::true_type{}, std::true_type{});
-  body(jt, std::true_type{}, std::false_type{});
+  for (; jt + 1 < n_main; jt += 2) {
+    tile(jt, 0, false, false, true);
+    tile(jt + 1, 1, false, false, true);
+  }
+  for (; jt < n_kv_tiles; ++jt)
+    tile(jt, jt & 1, 2 * jt + 1 >= n_full, 2 * jt + 2 >= n_full, false);
 
   // ---- epilogue: normalise, stage O through LDS for full-row stores, write LSE ----
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv = 1.f / l_tot;
-  char* stage = lds_k + wave * (32 * kRowBytes);   // 8 KiB per wave; all tiles are consumed
+  char* stage = lds + wave * (32 * kRowBytes);   // 8 KiB per wave; all tiles are consumed
 #pragma unroll
   for (int dc = 0; dc < 4; ++dc)
 #pragma unroll
