@@ -103,6 +103,10 @@ def main():
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-sweep", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="plan and KV transfer on a second stream, beside append and attention "
+                         "(default: the step's kernels run one after the other on one stream, so "
+                         "that each kernel's duration is its own)")
     ap.add_argument("--attention-only", metavar="WORKLOAD", default=None,
                     help="time only the attention kernel on one workload and exit (for profiling): "
                          + ", ".join(ATTN_WORKLOADS))
@@ -176,29 +180,51 @@ def main():
 
     attn_events = []
 
+    # With --overlap, two streams (both at the default priority).  main: append -> attention.
+    # side: plan (needs nothing from the step), then pack + unpack of the layer's KV as soon as
+    # the append is done, beside the attention (Sec. 3.5: a layer's KV is sent while the
+    # computation goes on).
+    args.serial = not args.overlap
+    main_s = torch.cuda.current_stream()
+    side_s = main_s if args.serial else torch.cuda.Stream()
+    ev = {k: torch.cuda.Event() for k in ("append", "plan", "attn", "xfer")}
+
     def step(record):
         # a1: page reservation for the new tokens (host free list; ids from the seeded tables
         # are the ones the kernels use, so the step is repeatable)
         got = [mc.mc_kv_alloc_pages(alloc, n) for n in new_pages]
         for g in reversed(got):
             mc.mc_kv_free_pages(alloc, g[::-1])
-        # a2: append the new tokens' K/V
-        mc.mc_kv_append(desc_a, 0, k_new, v_new, B, total_q, cu_q, begin, table, cu_pages)
-        # begin_forward + a3: attention of the new range over cache + itself
-        mc.mc_attn_plan(desc_a, Hq, B, total_q, cu_q, begin, table, cu_pages, ws, ws_bytes)
+        if not args.serial:
+            main_s.wait_event(ev["xfer"])     # the last step's pack has read the pages appended now
+            side_s.wait_event(ev["attn"])     # the last step's attention has read the work list
+        # begin_forward: plan the batch (side stream), a2: append the new tokens' K/V (main)
+        mc.mc_attn_plan(desc_a, Hq, B, total_q, cu_q, begin, table, cu_pages, ws, ws_bytes,
+                        stream=side_s)
+        mc.mc_kv_append(desc_a, 0, k_new, v_new, B, total_q, cu_q, begin, table, cu_pages,
+                        stream=main_s)
+        if not args.serial:
+            ev["plan"].record(side_s)
+            ev["append"].record(main_s)
+            main_s.wait_event(ev["plan"])
+            side_s.wait_event(ev["append"])
+        # a3: attention of the new range over cache + itself
         if record:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
+            e0.record(main_s)
         mc.mc_prefix_prefill_attn(desc_a, 0, q_new, Hq, B, total_q, cu_q, begin, table, cu_pages,
-                                  0.0, out, lse, ws, ws_bytes)
+                                  0.0, out, lse, ws, ws_bytes, stream=main_s)
         if record:
-            e1.record()
+            e1.record(main_s)
             attn_events.append((e0, e1))
         # a4 + a5: ship every sequence's KV [0, n) to the second pool (one launch each way)
         mc.mc_kv_pack_batch(desc_a, 0, 1, B, table, cu_pages, r_s0, r_s1, send_off,
-                            max_range_pages, send_all)
+                            max_range_pages, send_all, stream=side_s)
         mc.mc_kv_unpack_batch(desc_b, 0, 1, B, table_b, cu_pages_b, r_s0, r_s1, send_off,
-                              max_range_pages, send_all)
+                              max_range_pages, send_all, stream=side_s)
+        if not args.serial:
+            ev["attn"].record(main_s)
+            ev["xfer"].record(side_s)
 
     for _ in range(args.warmup):
         step(False)
@@ -319,7 +345,8 @@ def main():
                    "seed": args.seed, "total_new_tokens": total_q,
                    "total_tokens": int(np.sum(w.n)),
                    "useful_attention_flops_per_step": flops,
-                   "step": "alloc + append + plan + attention + pack_batch + unpack_batch"},
+                   "step": "alloc + append + plan + attention + pack_batch + unpack_batch",
+                   "streams": 2 if args.overlap else 1},
         "roofline": {"kernel": "attn_kernel<bf16, G=4>", "bound": "mfma",
                      "achieved": round(attn_tflops, 2), "peak": MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / MFMA_PEAK_TFLOPS, 4),
