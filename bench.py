@@ -30,8 +30,8 @@ ATTN_WORKLOADS = ["cfg2", "cfg3-passB", "cfg4", "cfg5-16k", "cfg5-32k", "paper-5
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very
 # command with the default seed (counters scaled by what a plain 4 GiB copy reads; see
 # profiles/bench_cfg2_hbm_traffic.md).  Valid only for the default workload.
-MEASURED_TRAFFIC = {"seed": 2000, "attention_bytes": int((355.6 + 79.8) * 2**20),
-                    "pack_4GiB_bytes": int((4096.2 + 4096.1) * 2**20)}
+MEASURED_TRAFFIC = {"seed": 2000, "attention_bytes": int((348.5 + 79.8) * 2**20),
+                    "pack_4GiB_bytes": int((4096.1 + 4096.1) * 2**20)}
 
 
 def attention_workload(name):
@@ -55,8 +55,10 @@ def attention_workload(name):
     raise SystemExit(f"unknown workload {name}; choose from {ATTN_WORKLOADS}")
 
 
-def attention_only(name, iters):
-    """Attention kernel alone on random resident KV: one JSON line.  For rocprofv3 runs."""
+def attention_only(name, iters, values="normal"):
+    """Attention kernel alone on resident Q/K/V: one JSON line.  For rocprofv3 runs.
+    values: "normal" = N(0,1) like the workload; "zero" = all zeros (same instructions, the
+    least operand switching: shows how far the data's power draw holds the clock down)."""
     import numpy as np
     import torch
 
@@ -65,10 +67,11 @@ def attention_only(name, iters):
     w = attention_workload(name)
     Hq, Hkv = w.num_q_heads, w.num_kv_heads
     up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    pool = torch.randn(w.num_pages * 2 * Hkv * 16 * 128, dtype=torch.bfloat16, device=dev)
+    gen = torch.randn if values == "normal" else torch.zeros
+    pool = gen(w.num_pages * 2 * Hkv * 16 * 128, dtype=torch.bfloat16, device=dev)
     desc = mc.pool_desc(pool, 1, w.num_pages, Hkv, w.dtype)
     tq = int(w.cu_q[-1])
-    q = torch.randn(tq * Hq * 128, dtype=torch.bfloat16, device=dev)
+    q = gen(tq * Hq * 128, dtype=torch.bfloat16, device=dev)
     cu_q, begin = up(w.cu_q), up(w.b.astype(np.int32))
     table, cu_pages = up(w.flat_page_table), up(w.cu_pages)
     wsb = mc.mc_attn_workspace_size(w.batch, tq, Hq, Hkv)
@@ -89,7 +92,8 @@ def attention_only(name, iters):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / iters
     fl = w.useful_flops()
-    print(json.dumps({"workload": w.name, "new_tokens": tq, "kv_tokens": int(np.sum(w.n)),
+    print(json.dumps({"workload": w.name, "values": values, "new_tokens": tq,
+                      "kv_tokens": int(np.sum(w.n)),
                       "useful_flops": fl, "ms": round(ms, 4),
                       "TFLOPs": round(fl / ms / 1e9, 1),
                       "frac_of_mfma_peak": round(fl / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}))
@@ -110,6 +114,8 @@ def main():
     ap.add_argument("--attention-only", metavar="WORKLOAD", default=None,
                     help="time only the attention kernel on one workload and exit (for profiling): "
                          + ", ".join(ATTN_WORKLOADS))
+    ap.add_argument("--values", choices=["normal", "zero"], default="normal",
+                    help="with --attention-only: Q/K/V values, N(0,1) or all zeros")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path has no cross-GPU step "
@@ -126,7 +132,7 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     if args.attention_only:
-        attention_only(args.attention_only, max(1, min(args.steps, 20)))
+        attention_only(args.attention_only, max(1, min(args.steps, 20)), args.values)
         return
 
     def up(a):
@@ -251,6 +257,24 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
+    # ---- MFMA issue rate of this GPU, alone, on constant operands and on operands drawn like
+    #      the workload's (the matrix pipes' power, and with it the clock, follows the data) ----
+    def mfma_rate(operands):
+        sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+        fl = [0]
+
+        def go():
+            fl[0] = mc.mc_mfma_probe(w.dtype, operands, 512, 1000, sink)
+        ms = timed(go, iters=5, warm=2)
+        return round(fl[0] / ms / 1e9, 1)
+
+    n_op = mc.mc_mfma_probe_operand_bytes() // 2
+    ops_const = torch.full((n_op,), 1.0, dtype=torch.bfloat16, device=dev)
+    ops_normal = up(mi.normal_bits(mi.rng_for(args.seed, 91), n_op, w.dtype))
+    mfma_measured = {"constant_operands_TFLOPs": mfma_rate(ops_const),
+                     "normal_operands_TFLOPs": mfma_rate(ops_normal)}
+    del ops_const, ops_normal
+
     # ---- copies, each alone: this workload, then the long-context transfer size ----
     copy = {}
     kv_bytes = int(np.sum(w.n)) * w.token_bytes
@@ -350,6 +374,7 @@ def main():
         "roofline": {"kernel": "attn_kernel<bf16, G=4>", "bound": "mfma",
                      "achieved": round(attn_tflops, 2), "peak": MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / MFMA_PEAK_TFLOPS, 4),
+                     "mfma_alone_measured": mfma_measured,
                      "traffic": MEASURED_TRAFFIC["attention_bytes"]
                      if args.seed == MEASURED_TRAFFIC["seed"] else None,
                      "algorithmic_bytes": 2 * total_q * Hq * D * 2 + total_q * Hq * 4

@@ -19,6 +19,7 @@ EXPORTS = [
     "mc_kv_append", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_check",
     "mc_prefix_prefill_attn", "mc_kv_pack_range", "mc_kv_unpack_range",
     "mc_kv_pack_batch", "mc_kv_unpack_batch",
+    "mc_mfma_probe_operand_bytes", "mc_mfma_probe",
 ]
 
 
@@ -68,6 +69,9 @@ def lib():
     L.mc_kv_unpack_range.argtypes = [pd, i32, i32, vp, i32, i32, i32, vp, vp]
     L.mc_kv_pack_batch.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
     L.mc_kv_unpack_batch.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
+    L.mc_mfma_probe_operand_bytes.argtypes = []
+    L.mc_mfma_probe_operand_bytes.restype = sz
+    L.mc_mfma_probe.argtypes = [i32, vp, i32, i32, vp, C.POINTER(i64), vp]
     _lib = L
     return L
 
@@ -208,3 +212,15 @@ def mc_kv_unpack_batch(pool: mc_pool_desc, layer_begin, layer_end, batch, page_t
                                     _ptr(page_table), _ptr(cu_pages), _ptr(s0), _ptr(s1),
                                     _ptr(buf_offset), max_range_pages, _ptr(sendbuf),
                                     _stream(stream)), "mc_kv_unpack_batch")
+
+
+def mc_mfma_probe_operand_bytes() -> int:
+    return int(lib().mc_mfma_probe_operand_bytes())
+
+
+def mc_mfma_probe(dtype, operands, blocks, iters, sink, stream=None) -> int:
+    """Launches the calibration kernel; returns the floating-point operations it issues."""
+    flops = C.c_int64(0)
+    _check(lib().mc_mfma_probe(dtype, _ptr(operands), blocks, iters, _ptr(sink), C.byref(flops),
+                               _stream(stream)), "mc_mfma_probe")
+    return int(flops.value)

@@ -161,3 +161,14 @@ def test_workspace_size():
     s1 = mc.mc_attn_workspace_size(4, 1000, 32, 8)
     s2 = mc.mc_attn_workspace_size(4, 2000, 32, 8)
     assert s2 > s1 and s1 % 16 == 0
+
+
+def test_mfma_probe_validation():
+    assert mc.mc_mfma_probe_operand_bytes() == 1 << 20
+    pr = mc.mc_mfma_probe
+    assert _status(pr, mc.MC_BF16, None, 4, 1, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pr, mc.MC_BF16, FAKE, 4, 1, None) == mc.MC_ERR_INVALID
+    assert _status(pr, mc.MC_BF16, FAKE + 2, 4, 1, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pr, mc.MC_BF16, FAKE, 0, 1, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pr, mc.MC_BF16, FAKE, 4, 0, FAKE) == mc.MC_ERR_INVALID
+    assert _status(pr, 7, FAKE, 4, 1, FAKE) == mc.MC_ERR_UNSUPPORTED
