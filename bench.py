@@ -25,7 +25,8 @@ HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
 
 
 ATTN_WORKLOADS = ["cfg2", "cfg3-passB", "cfg4", "cfg5-16k", "cfg5-32k", "paper-500-over-500",
-                  "paper-500-over-2500", "paper-500-over-4500"]
+                  "paper-500-over-2500", "paper-500-over-4500", "decode-8", "decode-64",
+                  "decode-256", "decode-64-plus-prefill"]
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very
 # command with the default seed (counters scaled by what a plain 4 GiB copy reads; see
@@ -52,6 +53,18 @@ def attention_workload(name):
         return w.with_ranges(b, n, name)
     if name.startswith("paper-500-over-"):
         return mi.paper_point(int(name.rsplit("-", 1)[1]))
+    if name.startswith("decode-"):
+        # one new token per sequence over contexts ~ U[1024, 4096] (Llama-3-8B shapes), alone or
+        # in one ragged batch with a 2048-token prefill range over 1024 cached tokens
+        batch = int(name.split("-")[1])
+        rng = mi.rng_for(4242, batch)
+        n = rng.integers(1024, 4097, size=batch)
+        b = n - 1
+        if name.endswith("-plus-prefill"):
+            n, b = np.append(n, 3072), np.append(b, 1024)
+        w = mi.Workload(name, 4242, mi.BF16, 1, 32, 8, 65536, n, b)
+        w.page_tables = mi.scatter_page_tables(mi.rng_for(4242, mi.KIND_TABLE), 65536, n)
+        return w
     raise SystemExit(f"unknown workload {name}; choose from {ATTN_WORKLOADS}")
 
 
@@ -92,8 +105,10 @@ def attention_only(name, iters, values="normal"):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / iters
     fl = w.useful_flops()
+    alg_bytes = 2 * tq * Hq * 256 + tq * Hq * 4 + int(np.sum(w.n)) * w.token_bytes
     print(json.dumps({"workload": w.name, "values": values, "new_tokens": tq,
                       "kv_tokens": int(np.sum(w.n)),
+                      "algorithmic_GBps": round(alg_bytes / ms / 1e6, 1),
                       "useful_flops": fl, "ms": round(ms, 4),
                       "TFLOPs": round(fl / ms / 1e9, 1),
                       "frac_of_mfma_peak": round(fl / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}))

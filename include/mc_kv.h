@@ -139,8 +139,16 @@ mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer,
  * ragged batch into a work list in `workspace`, validates the device arrays and
  * is valid for every layer as long as the arrays it was given are unchanged.
  * mc_prefix_prefill_attn requires a workspace planned with the same arguments.
- * mc_attn_workspace_size gives the bytes needed (0 on bad arguments);
- * workspace must be 16-byte aligned. */
+ * When a batch has too few (new token, kv head) tiles to fill the GPU - decode
+ * steps (one new token per sequence, Sec. 3.3: the prefill of the remaining
+ * prompt is fused with decode), short ranges over long contexts - the plan
+ * cuts long KV ranges into chunks that run side by side; the attention call
+ * then keeps the chunks' partial results in the workspace and merges them
+ * (by their log-sum-exp) before it returns control of the stream.  Calls that
+ * use one workspace must therefore run one after the other, never concurrently.
+ * mc_attn_workspace_size gives the bytes needed (0 on bad arguments; room
+ * for those partial results, at most 128 MiB, is part of it unless the batch is
+ * large enough never to need them); workspace must be 16-byte aligned. */
 size_t mc_attn_workspace_size(int32_t batch, int32_t total_q, int32_t num_q_heads,
                               int32_t num_kv_heads);
 mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
@@ -163,7 +171,7 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer,
                                  float sm_scale /* 0 -> 1/sqrt(D) */,
                                  void* out /* device [total_q][Hq][D], pool dtype */,
                                  float* lse /* device [total_q][Hq] */,
-                                 const void* workspace, size_t workspace_bytes, void* stream);
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- transfer payload: pages <-> contiguous buffer -------------------------
  * (sender and receiver side of remote_send: KV of prompt[begin:end] goes to the

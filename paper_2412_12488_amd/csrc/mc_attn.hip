@@ -49,28 +49,69 @@ constexpr int32_t kPlanMagic = 0x6d63706c;
 struct PlanHeader {
   int32_t magic;
   int32_t err;        // mc_status found on the device by the plan kernel
-  int32_t num_tiles;  // q tiles in the work list
+  int32_t num_items;  // work items (q tile x KV chunk) in the work list
   int32_t tile_tokens;
   int32_t batch;
   int32_t total_q;
-  int32_t pad[10];
+  int32_t num_merges; // q tiles whose KV range was cut into several chunks
+  int32_t chunk_tiles;  // chunk length the planner settled on (KV tiles); 0 = nothing was cut
+  int32_t pad[8];
 };
 static_assert(sizeof(PlanHeader) == 64, "header is 64 bytes");
 
-struct WorkspaceLayout {
-  size_t cu_tiles, tile_seq, tile_row0, total;
-  int32_t max_tiles;
+// One work item: q tile (seq, row0) over the KV tiles [t0, t1) of its sequence.  t0 is even.
+// part < 0: the item covers the tile's whole KV range and writes out/lse itself.  Otherwise it
+// writes a partial result (O normalised within the chunk, fp32, and the chunk's LSE) for token
+// tt of the tile at row part + tt of the partial arrays, and merge_kernel combines the chunks.
+struct ItemRec {
+  int32_t seq, row0, t0, t1, part, pad[3];
+};
+static_assert(sizeof(ItemRec) == 32, "item record is 32 bytes");
+
+// One q tile that was cut: chunk c's partial rows start at part + c * ntok.
+struct MergeRec {
+  int32_t q_row;   // index of the tile's first token among all new tokens of the batch
+  int32_t ntok, nsplit, part;
 };
 
-inline size_t round16(size_t x) { return (x + 15) & ~size_t(15); }
+constexpr int kMinChunkTiles = 8;     // never cut a KV range into pieces shorter than 512 keys
+constexpr int kRoundsWanted = 4;      // cut only while the launch has fewer items than 4 per slot
 
-inline WorkspaceLayout workspace_layout(int32_t batch, int32_t total_q, int32_t tile_tokens) {
+struct WorkspaceLayout {
+  size_t cu_tiles, items, merges, part_lse, part_o, total;
+  int32_t max_tiles, max_items, part_cap, batch;
+};
+
+inline size_t round64(size_t x) { return (x + 63) & ~size_t(63); }
+
+constexpr int kMaxSlots = 1024;   // 512 compute units: beyond any GPU this library is written for
+constexpr size_t kPartialBytesCap = size_t(128) << 20;
+
+// Token rows the partial arrays can hold: the planner cuts KV ranges only as far as this
+// allows.  None when the batch has so many q tiles that no GPU would need a cut; otherwise two
+// chunks for every new token plus room for the many chunks of a few decode rows, within 128 MiB.
+inline int32_t partial_capacity(int32_t total_q, int32_t tile_tokens, int32_t num_q_heads,
+                                int32_t num_kv_heads) {
+  const int64_t tiles = ((int64_t)total_q + tile_tokens - 1) / tile_tokens;
+  if (tiles * num_kv_heads >= (int64_t)kRoundsWanted * kMaxSlots) return 0;
+  const int64_t want = 2ll * total_q + 4096;
+  const int64_t fit = (int64_t)(kPartialBytesCap / (sizeof(float) * num_q_heads * (mc::kHeadDim + 1)));
+  return (int32_t)(want < fit ? want : fit);
+}
+
+inline WorkspaceLayout workspace_layout(int32_t batch, int32_t total_q, int32_t tile_tokens,
+                                        int32_t num_q_heads, int32_t num_kv_heads) {
   WorkspaceLayout w;
   w.max_tiles = (int32_t)(((int64_t)total_q + tile_tokens - 1) / tile_tokens + batch);
+  w.part_cap = partial_capacity(total_q, tile_tokens, num_q_heads, num_kv_heads);
+  w.batch = batch;
+  w.max_items = w.max_tiles + w.part_cap;   // every extra chunk holds at least one partial row
   w.cu_tiles = sizeof(PlanHeader);
-  w.tile_seq = w.cu_tiles + round16(sizeof(int32_t) * ((size_t)batch + 1));
-  w.tile_row0 = w.tile_seq + round16(sizeof(int32_t) * (size_t)w.max_tiles);
-  w.total = w.tile_row0 + round16(sizeof(int32_t) * (size_t)w.max_tiles);
+  w.items = w.cu_tiles + round64(sizeof(int32_t) * ((size_t)batch + 1));
+  w.merges = w.items + sizeof(ItemRec) * (size_t)w.max_items;
+  w.part_lse = w.merges + round64(sizeof(MergeRec) * (size_t)w.max_tiles);
+  w.part_o = w.part_lse + round64(sizeof(float) * (size_t)w.part_cap * num_q_heads);
+  w.total = w.part_o + sizeof(float) * (size_t)w.part_cap * num_q_heads * mc::kHeadDim;
   return w;
 }
 
@@ -82,9 +123,10 @@ struct PlanArgs {
   const int32_t* cu_pages;
   PlanHeader* hdr;
   int32_t* cu_tiles;
-  int32_t* tile_seq;
-  int32_t* tile_row0;
-  int32_t batch, total_q, tile_tokens, num_pages, max_tiles;
+  ItemRec* items;
+  MergeRec* merges;
+  int32_t batch, total_q, tile_tokens, num_pages, max_tiles, max_items, part_cap;
+  int32_t hkv, slots;   // kv heads; workgroups the GPU runs at a time
 };
 
 // Block-wide exclusive scan of one value per thread (kPlanThreads threads).
@@ -104,16 +146,18 @@ __device__ int block_exclusive_scan(int v, int* lds, int* total) {
   return incl - v;
 }
 
-// One workgroup.  Validates the ragged-batch arrays, cuts every sequence's new
-// range into q tiles of tile_tokens tokens and orders the tiles by decreasing
-// number of KV tiles (longest first), so that the tail of the launch is made of
-// short work items.
+// One workgroup.  Validates the ragged-batch arrays, cuts every sequence's new range into q
+// tiles of tile_tokens tokens, cuts long KV ranges into chunks when the launch would otherwise
+// have too few work items to fill the GPU (decode rows, short batches over long contexts),
+// and orders the items by decreasing number of KV tiles (longest first), so that the tail of
+// the launch is made of short items.
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   __shared__ int scan[kPlanThreads];
   __shared__ int hist[kBuckets];
-  __shared__ int s_err, s_maxcost;
+  __shared__ int s_err, s_maxcost, s_chunk, s_part_tokens;
+  __shared__ unsigned long long s_cost;
   const int t = threadIdx.x;
-  if (t == 0) { s_err = 0; s_maxcost = 1; }
+  if (t == 0) { s_err = 0; s_maxcost = 1; s_cost = 0; s_chunk = 0; s_part_tokens = 0; }
   for (int i = t; i < kBuckets; i += kPlanThreads) hist[i] = 0;
   __syncthreads();
 
@@ -136,7 +180,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   atomicMax(&s_maxcost, maxcost);
   __syncthreads();
   if (s_err) {
-    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_tiles = 0; a.hdr->magic = kPlanMagic; }
+    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
     return;
   }
   // 2. page ids of every needed table entry (one wavefront per sequence at a time)
@@ -162,30 +206,82 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   __threadfence_block();
   __syncthreads();
   if (s_err || total_tiles > a.max_tiles) {
-    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_tiles = 0; a.hdr->magic = kPlanMagic; }
+    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
     return;
   }
-  // 4. counting sort of tiles by cost (number of KV tiles), heaviest first
-  int shift = 0;
-  while ((s_maxcost >> shift) >= kBuckets) ++shift;
-  auto locate = [&](int i, int& s, int& row0, int& bucket) {
+
+  // q tile i: its sequence, first row, token count, KV tiles, and the last even tile index at
+  // which a chunk may start (every row must see at least the first key of every chunk)
+  struct Tile { int s, row0, ntok, T, dmax; };
+  auto locate = [&](int i) {
     int lo = 0, hi = a.batch;
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
       if (a.cu_tiles[mid] <= i) lo = mid; else hi = mid;
     }
-    s = lo;
-    row0 = (i - a.cu_tiles[s]) * a.tile_tokens;
-    const int q = a.cu_q[s + 1] - a.cu_q[s];
-    const int kv_len = a.begin[s] + min(q, row0 + a.tile_tokens);
-    bucket = kBuckets - 1 - (((kv_len + kBN - 1) / kBN) >> shift);
+    Tile x;
+    x.s = lo;
+    x.row0 = (i - a.cu_tiles[lo]) * a.tile_tokens;
+    const int q = a.cu_q[lo + 1] - a.cu_q[lo], b = a.begin[lo];
+    x.ntok = min(a.tile_tokens, q - x.row0);
+    x.T = (b + x.row0 + x.ntok + kBN - 1) / kBN;
+    x.dmax = ((b + x.row0) / kBN) & ~1;
+    return x;
   };
-  for (int i = t; i < total_tiles; i += kPlanThreads) {
-    int s, row0, bucket;
-    locate(i, s, row0, bucket);
-    atomicAdd(&hist[bucket], 1);
+  // chunks of L tiles (L even): [0,L), [L,2L), ..., [kL, T) with k = dmax / L
+  auto splits_of = [&](const Tile& x, int L) { return L > 0 ? x.dmax / L + 1 : 1; };
+
+  // 4. chunk length.  No cutting when the q tiles alone give the GPU kRoundsWanted rounds of
+  //    work; otherwise aim for that many items, never below kMinChunkTiles, and double the
+  //    length until the partial rows fit the workspace.
+  int L = 0;
+  if ((int64_t)total_tiles * a.hkv < (int64_t)kRoundsWanted * a.slots) {
+    unsigned long long cost = 0;
+    for (int i = t; i < total_tiles; i += kPlanThreads) cost += locate(i).T;
+    atomicAdd(&s_cost, cost);
+    __syncthreads();
+    const long long want = (long long)((s_cost * a.hkv + (unsigned long long)kRoundsWanted * a.slots - 1) /
+                                       ((unsigned long long)kRoundsWanted * a.slots));
+    L = want < kMinChunkTiles ? kMinChunkTiles : want > (1 << 28) ? (1 << 28) : (int)want;
+    L = (L + 1) & ~1;
+    for (;;) {
+      if (L >= s_maxcost) { L = 0; break; }   // nothing is long enough to be cut
+      int tokens = 0;
+      for (int i = t; i < total_tiles; i += kPlanThreads) {
+        const Tile x = locate(i);
+        const int ns = splits_of(x, L);
+        if (ns > 1) tokens += ns * x.ntok;
+      }
+      __syncthreads();
+      if (t == 0) s_part_tokens = 0;
+      __syncthreads();
+      atomicAdd(&s_part_tokens, tokens);
+      __syncthreads();
+      if (s_part_tokens <= a.part_cap) break;
+      L *= 2;
+    }
   }
-  __syncthreads();
+
+  // 5. items and merge records: count per contiguous range of tiles, scan, histogram of costs
+  const int tper = (total_tiles + kPlanThreads - 1) / kPlanThreads;
+  const int i_lo = min(t * tper, total_tiles), i_hi = min(i_lo + tper, total_tiles);
+  int shift = 0;
+  while ((s_maxcost >> shift) >= kBuckets) ++shift;
+  int n_items = 0, n_part = 0, n_merge = 0;
+  for (int i = i_lo; i < i_hi; ++i) {
+    const Tile x = locate(i);
+    const int ns = splits_of(x, L);
+    n_items += ns;
+    if (ns > 1) { n_part += ns * x.ntok; ++n_merge; }
+    for (int c = 0; c < ns; ++c) {
+      const int len = (c + 1 < ns ? L : x.T - c * L);
+      atomicAdd(&hist[kBuckets - 1 - (len >> shift)], 1);
+    }
+  }
+  int tot_items, tot_part, tot_merge;
+  block_exclusive_scan(n_items, scan, &tot_items);
+  int part_off = block_exclusive_scan(n_part, scan, &tot_part);
+  int merge_off = block_exclusive_scan(n_merge, scan, &tot_merge);
   {
     constexpr int kPer = kBuckets / kPlanThreads;
     int local[kPer], sum = 0;
@@ -194,16 +290,40 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     for (int i = 0; i < kPer; ++i) { hist[t * kPer + i] = off; off += local[i]; }
   }
   __syncthreads();
-  for (int i = t; i < total_tiles; i += kPlanThreads) {
-    int s, row0, bucket;
-    locate(i, s, row0, bucket);
-    const int pos = atomicAdd(&hist[bucket], 1);
-    a.tile_seq[pos] = s;
-    a.tile_row0[pos] = row0;
+  if (tot_items > a.max_items || tot_part > a.part_cap || tot_merge > a.max_tiles) {   // cannot happen
+    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
+    return;
+  }
+  // 6. emit: counting sort of the items by cost (number of KV tiles), heaviest first
+  for (int i = i_lo; i < i_hi; ++i) {
+    const Tile x = locate(i);
+    const int ns = splits_of(x, L);
+    if (ns > 1) {
+      MergeRec m;
+      m.q_row = a.cu_q[x.s] + x.row0;
+      m.ntok = x.ntok;
+      m.nsplit = ns;
+      m.part = part_off;
+      a.merges[merge_off++] = m;
+    }
+    for (int c = 0; c < ns; ++c) {
+      ItemRec it;
+      it.seq = x.s;
+      it.row0 = x.row0;
+      it.t0 = c * L;
+      it.t1 = (c + 1 < ns ? (c + 1) * L : x.T);
+      it.part = ns > 1 ? part_off + c * x.ntok : -1;
+      it.pad[0] = it.pad[1] = it.pad[2] = 0;
+      const int pos = atomicAdd(&hist[kBuckets - 1 - ((it.t1 - it.t0) >> shift)], 1);
+      a.items[pos] = it;
+    }
+    if (ns > 1) part_off += ns * x.ntok;
   }
   if (t == 0) {
     a.hdr->err = MC_OK;
-    a.hdr->num_tiles = total_tiles;
+    a.hdr->num_items = tot_items;
+    a.hdr->num_merges = tot_merge;
+    a.hdr->chunk_tiles = L;
     a.hdr->tile_tokens = a.tile_tokens;
     a.hdr->batch = a.batch;
     a.hdr->total_q = a.total_q;
@@ -250,8 +370,9 @@ struct AttnArgs {
   const int32_t* page_table;
   const int32_t* cu_pages;
   const PlanHeader* hdr;
-  const int32_t* tile_seq;
-  const int32_t* tile_row0;
+  const ItemRec* items;
+  float* part_lse;         // [partial row][hq]
+  float* part_o;           // [partial row][hq][128]
   int64_t page_stride;     // bytes
   int32_t num_pages, hkv, hq, batch, total_q;
   float scale, scale_log2;  // softmax scale, and scale * log2(e)
@@ -318,7 +439,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const int hk = blockIdx.x % a.hkv;
   const int wi = blockIdx.x / a.hkv;
   // the work list must come from a plan made for this very batch
-  if (a.hdr->magic != kPlanMagic || wi >= a.hdr->num_tiles || a.hdr->tile_tokens != TOK ||
+  if (a.hdr->magic != kPlanMagic || wi >= a.hdr->num_items || a.hdr->tile_tokens != TOK ||
       a.hdr->batch != a.batch || a.hdr->total_q != a.total_q)
     return;
 
@@ -326,12 +447,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
 
-  const int seq = a.tile_seq[wi], row0 = a.tile_row0[wi];
+  typedef int32_t i32x8 __attribute__((ext_vector_type(8)));
+  const i32x8 item = *(const __attribute__((address_space(4))) i32x8*)(a.items + wi);
+  const int seq = item[0], row0 = item[1];
+  const int t0 = item[2];                            // first KV tile of the item (even)
+  const int part = item[4];                          // >= 0: partial result, merged afterwards
   const int q0 = a.cu_q[seq], q_len = a.cu_q[seq + 1] - q0, b = a.begin[seq];
   const int ntok = min(TOK, q_len - row0);          // valid tokens in this tile (>= 1)
   const int first_pos = b + row0;                    // position of the tile's first token
-  const int kv_len = first_pos + ntok;               // keys [0, kv_len) are needed
-  const int n_kv_tiles = (kv_len + kBN - 1) / kBN;
+  // keys [64 t0, kv_len) are this item's: up to the end of its chunk, or of the tile's range
+  const int kv_len = min(first_pos + ntok, item[3] * kBN);
+  const int n_kv_tiles = (kv_len + kBN - 1) / kBN;   // (absolute) index after the last KV tile
   const int n_halves = (kv_len + kHalf - 1) / kHalf;
   // half h is fully visible to every row of the q tile iff 32 (h+1) <= first_pos + 1
   const int n_full = (first_pos + 1) / kHalf;
@@ -451,17 +577,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     // table entries 0..5 (K halves 0..2), 0..3 (V tile 0)
     const char* pb[6];
 #pragma unroll
-    for (int i = 0; i < 6; ++i) pb[i] = page_base(table[min(i, last_pidx)]);
+    for (int i = 0; i < 6; ++i) pb[i] = page_base(table[min(4 * t0 + i, last_pidx)]);
 #pragma unroll
     for (int i = 0; i < 6; ++i) copy_page(pb[i], false, lds_k + i * 4096);
 #pragma unroll
     for (int i = 0; i < 4; ++i) copy_page(pb[i], true, lds_v + i * 4096);
   }
-  ids_next = fetch_ids(4);
+  ids_next = fetch_ids(4 * t0 + 4);
   wait_copies_and_sync();
 #pragma unroll
   for (int f = 0; f < 8; ++f) s_a = Mfma<T>::run(k_frag(lds_k, f), qreg[f], f == 0 ? zero16 : s_a);
-  if (n_full == 0) mask_half(0, s_a);
+  if (n_full <= 2 * t0) mask_half(2 * t0, s_a);
   {
     float mx = s_a[0];
 #pragma unroll
@@ -573,8 +699,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 
   // Tiles whose two half steps need no mask on their successor halves (2j+1, 2j+2 below the
   // diagonal) run two per iteration with constant LDS addresses; the rest follow one by one.
-  const int n_main = max(0, min(n_full - 2, 2 * n_kv_tiles - 2) / 2);   // tiles j with 2j+2 < n_full
-  int jt = 0;
+  const int n_main = max(t0, min(n_full - 2, 2 * n_kv_tiles - 2) / 2);   // tiles j with 2j+2 < n_full
+  int jt = t0;
   for (; jt + 1 < n_main; jt += 2) {
     tile(jt, 0, false, false, true);
     tile(jt + 1, 1, false, false, true);
@@ -585,6 +711,26 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   // ---- epilogue: normalise, stage O through LDS for full-row stores, write LSE ----
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv = 1.f / l_tot;
+  if (part >= 0) {
+    // One chunk of a cut KV range: O normalised within the chunk (fp32) and the chunk's LSE go
+    // to the partial arrays; merge_kernel weighs the chunks together.  A lane holds, for its
+    // row, d = 32 dc + 8 j + 4 half + {0..3}: 16 bytes per (dc, j).
+    if (row_ok) {
+      const int64_t prow = (int64_t)(part + tt) * a.hq + hk * G + g;
+      float* po = a.part_o + prow * mc::kHeadDim;
+#pragma unroll
+      for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          typedef float f32x4 __attribute__((ext_vector_type(4)));
+          f32x4 v = {o_acc[dc][4 * j] * inv, o_acc[dc][4 * j + 1] * inv, o_acc[dc][4 * j + 2] * inv,
+                     o_acc[dc][4 * j + 3] * inv};
+          *reinterpret_cast<f32x4*>(po + 32 * dc + 8 * j + 4 * half) = v;
+        }
+      if (half == 0) a.part_lse[prow] = m_run * a.scale + __logf(l_tot);
+    }
+    return;
+  }
   char* stage = lds + wave * (32 * kRowBytes);   // 8 KiB per wave; all tiles are consumed
 #pragma unroll
   for (int dc = 0; dc < 4; ++dc)
@@ -611,6 +757,50 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   }
 }
 
+// Combines the chunks of every q tile whose KV range was cut: with L_c the chunk LSEs,
+// LSE = log sum_c exp(L_c) and O = sum_c exp(L_c - LSE) O_c.  One workgroup per (cut tile,
+// token), one wavefront per q head at a time, two d per lane; a chunk's loads do not depend on
+// another chunk's, so they are all in flight together.
+struct MergeArgs {
+  const PlanHeader* hdr;
+  const MergeRec* merges;
+  const float* part_lse;
+  const float* part_o;
+  char* out;
+  float* lse;
+  int32_t hq;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+  if (a.hdr->magic != kPlanMagic || (int)blockIdx.x >= a.hdr->num_merges) return;
+  const MergeRec m = a.merges[blockIdx.x];
+  const int tt = blockIdx.y;
+  if (tt >= m.ntok) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  for (int h = wave; h < a.hq; h += 4) {
+    float mx = -INFINITY;
+    for (int c = 0; c < m.nsplit; ++c)
+      mx = fmaxf(mx, a.part_lse[(int64_t)(m.part + c * m.ntok + tt) * a.hq + h]);
+    float den = 0.f;
+    f32x2 acc = {0.f, 0.f};
+#pragma unroll 4
+    for (int c = 0; c < m.nsplit; ++c) {
+      const int64_t prow = (int64_t)(m.part + c * m.ntok + tt) * a.hq + h;
+      const float w = __expf(a.part_lse[prow] - mx);   // exp(-inf) = 0 for a chunk with no key
+      const f32x2 v = *reinterpret_cast<const f32x2*>(a.part_o + prow * mc::kHeadDim + 2 * lane);
+      den += w;
+      acc += v * w;
+    }
+    const float inv = 1.f / den;
+    const int64_t orow = (int64_t)(m.q_row + tt) * a.hq + h;
+    *reinterpret_cast<uint32_t*>(a.out + orow * kRowBytes + 4 * lane) =
+        Mfma<T>::pack2(acc[0] * inv, acc[1] * inv);
+    if (lane == 0) a.lse[orow] = mx + __logf(den);
+  }
+}
+
 template <typename T>
 mc_status launch_attn(int G, dim3 grid, hipStream_t hs, const AttnArgs& a) {
   switch (G) {
@@ -621,6 +811,29 @@ mc_status launch_attn(int G, dim3 grid, hipStream_t hs, const AttnArgs& a) {
     default: return MC_ERR_UNSUPPORTED;
   }
   return mc::launch_status();
+}
+
+// Workgroups of the attention kernel the current GPU runs at a time: two per compute unit.
+int device_slots() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return -1;
+  return 2 * cus;
+}
+
+// The planner cuts KV ranges only if the q tiles times kv heads are fewer than kRoundsWanted per
+// slot; the number of q tiles is at least total_q / tile_tokens, which the host knows.
+bool may_cut(const WorkspaceLayout& w, int hkv, int slots) {
+  return w.part_cap > 0 && (int64_t)(w.max_tiles - w.batch) * hkv < (int64_t)kRoundsWanted * slots;
+}
+
+// Upper bound of the planner's item count: a q tile with T KV tiles becomes at most T / L + 1
+// items, and the planner's chunk length L is at least (sum of T) x hkv / (kRoundsWanted x slots).
+int32_t item_bound(const WorkspaceLayout& w, int hkv, int slots) {
+  if (!may_cut(w, hkv, slots)) return w.max_tiles;
+  const int64_t b = (int64_t)w.max_tiles + (int64_t)kRoundsWanted * slots / hkv + 1;
+  return (int32_t)(b < w.max_items ? b : w.max_items);
 }
 
 mc_status check_attn_shape(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
@@ -645,7 +858,7 @@ size_t mc_attn_workspace_size(int32_t batch, int32_t total_q, int32_t num_q_head
   if (num_q_heads % num_kv_heads != 0) return 0;
   const int G = num_q_heads / num_kv_heads;
   if (G != 1 && G != 2 && G != 4 && G != 8) return 0;
-  return workspace_layout(batch, total_q, kBM / G).total;
+  return workspace_layout(batch, total_q, kBM / G, num_q_heads, num_kv_heads).total;
 }
 
 mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
@@ -656,7 +869,8 @@ mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t ba
   mc_status st = check_attn_shape(pool, num_q_heads, batch, total_q, &G);
   if (st != MC_OK) return st;
   if (!workspace || !mc::aligned16(workspace)) return MC_ERR_INVALID;
-  const WorkspaceLayout w = workspace_layout(batch, total_q, kBM / G);
+  const WorkspaceLayout w =
+      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads);
   if (workspace_bytes < w.total) return MC_ERR_INVALID;
   if (batch > 0 && (!cu_q || !begin || !page_table || !cu_pages)) return MC_ERR_INVALID;
   if (batch == 0) {   // nothing to plan: a header with an empty work list
@@ -670,13 +884,18 @@ mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t ba
   a.cu_pages = cu_pages;
   a.hdr = reinterpret_cast<PlanHeader*>(ws);
   a.cu_tiles = reinterpret_cast<int32_t*>(ws + w.cu_tiles);
-  a.tile_seq = reinterpret_cast<int32_t*>(ws + w.tile_seq);
-  a.tile_row0 = reinterpret_cast<int32_t*>(ws + w.tile_row0);
+  a.items = reinterpret_cast<ItemRec*>(ws + w.items);
+  a.merges = reinterpret_cast<MergeRec*>(ws + w.merges);
   a.batch = batch;
   a.total_q = total_q;
   a.tile_tokens = kBM / G;
   a.num_pages = pool->num_pages;
   a.max_tiles = w.max_tiles;
+  a.hkv = pool->num_kv_heads;
+  a.slots = device_slots();
+  if (a.slots <= 0) return MC_ERR_HIP;
+  a.max_items = item_bound(w, a.hkv, a.slots);
+  a.part_cap = w.part_cap;
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0,
                      static_cast<hipStream_t>(stream), a);
   return mc::launch_status();
@@ -697,7 +916,7 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
                                  int32_t num_q_heads, int32_t batch, int32_t total_q,
                                  const int32_t* cu_q, const int32_t* begin,
                                  const int32_t* page_table, const int32_t* cu_pages,
-                                 float sm_scale, void* out, float* lse, const void* workspace,
+                                 float sm_scale, void* out, float* lse, void* workspace,
                                  size_t workspace_bytes, void* stream) {
   int G = 0;
   mc_status st = check_attn_shape(pool, num_q_heads, batch, total_q, &G);
@@ -710,11 +929,14 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
   if (!mc::aligned16(q) || !mc::aligned16(out) || !mc::aligned16(workspace) ||
       (reinterpret_cast<uintptr_t>(lse) & 3u))
     return MC_ERR_INVALID;
-  const WorkspaceLayout w = workspace_layout(batch, total_q, kBM / G);
+  const WorkspaceLayout w =
+      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads);
   if (workspace_bytes < w.total) return MC_ERR_INVALID;
-  const int64_t blocks = (int64_t)w.max_tiles * pool->num_kv_heads;
+  const int slots = device_slots();
+  if (slots <= 0) return MC_ERR_HIP;
+  const int64_t blocks = (int64_t)item_bound(w, pool->num_kv_heads, slots) * pool->num_kv_heads;
   if (blocks > 0x7fffffffll) return MC_ERR_UNSUPPORTED;
-  const char* ws = static_cast<const char*>(workspace);
+  char* ws = static_cast<char*>(workspace);
   AttnArgs a;
   a.pool_layer = static_cast<const char*>(pool->base) + layer * mc::layer_stride_bytes(pool);
   a.q = static_cast<const char*>(q);
@@ -725,8 +947,9 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
   a.page_table = page_table;
   a.cu_pages = cu_pages;
   a.hdr = reinterpret_cast<const PlanHeader*>(ws);
-  a.tile_seq = reinterpret_cast<const int32_t*>(ws + w.tile_seq);
-  a.tile_row0 = reinterpret_cast<const int32_t*>(ws + w.tile_row0);
+  a.items = reinterpret_cast<const ItemRec*>(ws + w.items);
+  a.part_lse = reinterpret_cast<float*>(ws + w.part_lse);
+  a.part_o = reinterpret_cast<float*>(ws + w.part_o);
   a.page_stride = mc::page_stride_bytes(pool);
   a.num_pages = pool->num_pages;
   a.hkv = pool->num_kv_heads;
@@ -737,8 +960,23 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
   a.scale_log2 = a.scale * 1.4426950408889634f;
   dim3 grid((unsigned)blocks);
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  if (pool->dtype == MC_F16) return launch_attn<_Float16>(G, grid, hs, a);
-  return launch_attn<__bf16>(G, grid, hs, a);
+  st = pool->dtype == MC_F16 ? launch_attn<_Float16>(G, grid, hs, a)
+                             : launch_attn<__bf16>(G, grid, hs, a);
+  if (st != MC_OK || !may_cut(w, pool->num_kv_heads, slots)) return st;
+  // the planner may have cut KV ranges: weigh the chunks together (does nothing if it did not)
+  MergeArgs m;
+  m.hdr = a.hdr;
+  m.merges = reinterpret_cast<const MergeRec*>(ws + w.merges);
+  m.part_lse = a.part_lse;
+  m.part_o = a.part_o;
+  m.out = a.out;
+  m.lse = a.lse;
+  m.hq = num_q_heads;
+  if (pool->dtype == MC_F16)
+    hipLaunchKernelGGL(merge_kernel<_Float16>, dim3(w.max_tiles, kBM / G), dim3(256), 0, hs, m);
+  else
+    hipLaunchKernelGGL(merge_kernel<__bf16>, dim3(w.max_tiles, kBM / G), dim3(256), 0, hs, m);
+  return mc::launch_status();
 }
 
 }  // extern "C"

@@ -323,3 +323,52 @@ def test_mfma_probe_counts_and_runs():
     # per lane: 4 accumulators x 16 elements, each = (iters * 64 / 4) instructions x 16 products
     expect = 4 * 16 * (iters * 64 // 4) * 16
     assert torch.all(sink == float(expect)), (sink[:4], expect)
+
+
+# ------------------------------------------------- cut KV ranges (decode rows, short batches) ----
+def plan_header(w):
+    pool = DevPool(w)
+    db = DevBatch(w)
+    ws_bytes = mc.mc_attn_workspace_size(db.batch, db.total_q, w.num_q_heads, w.num_kv_heads)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    mc.mc_attn_plan(pool.desc, w.num_q_heads, db.batch, db.total_q, db.cu_q, db.begin,
+                    db.page_table, db.cu_pages, ws, ws_bytes)
+    mc.mc_attn_plan_check(ws)
+    h = ws[:64].view(torch.int32).cpu().numpy()
+    return {"num_items": int(h[2]), "tile_tokens": int(h[3]), "num_merges": int(h[6]),
+            "chunk_tiles": int(h[7])}
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype", [(32, 8, mi.BF16), (8, 8, mi.F16), (64, 8, mi.BF16)])
+def test_decode_rows_fused_with_prefill(Hq, Hkv, dtype):
+    # decode steps (one new token over contexts of 1..5000 tokens) in one ragged batch with two
+    # prefill ranges and an idle sequence (Sec. 3.3: the prefill of the rest of a prompt runs
+    # fused with decode).  Too few q tiles to fill the GPU: the planner cuts the long contexts
+    # into chunks and the chunks' partial results are merged by their LSE.
+    lens = [1, 17, 64, 65, 1000, 2047, 2049, 5000, 1500, 700, 90]
+    begins = [0, 16, 63, 64, 999, 2046, 2048, 4999, 300, 0, 90]
+    w = small_workload(300 + Hq, dtype, Hq, Hkv, lens, begins)
+    h = plan_header(w)
+    assert h["chunk_tiles"] >= 8 and h["chunk_tiles"] % 2 == 0 and h["num_merges"] > 0, h
+    check_attention(w)
+
+
+def test_pure_decode_batch():
+    rng = mi.rng_for(321)
+    lens = [int(x) for x in rng.integers(1, 4097, size=48)]
+    w = small_workload(322, mi.BF16, 32, 8, lens, [n - 1 for n in lens])
+    h = plan_header(w)
+    assert h["num_merges"] > 0 and h["num_items"] > 48, h
+    check_attention(w)
+
+
+def test_large_batch_is_not_cut():
+    h = plan_header(mi.config(2))
+    assert h["chunk_tiles"] == 0 and h["num_merges"] == 0 and h["num_items"] >= 300, h
+
+
+def test_short_range_over_long_context_is_cut():
+    w = mi.paper_point(4500)
+    h = plan_header(w)
+    assert h["num_merges"] > 0, h
+    check_attention(w, sample=256, seed=9)

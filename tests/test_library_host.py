@@ -155,7 +155,9 @@ def test_validation_rejects_before_launch():
 
 def test_workspace_size():
     assert mc.mc_attn_workspace_size(1, 16, 32, 8) >= 64 + 8
-    assert mc.mc_attn_workspace_size(8, 20000, 32, 8) < (1 << 20)
+    assert mc.mc_attn_workspace_size(8, 20000, 32, 8) < (1 << 20)      # many q tiles: no partials
+    assert mc.mc_attn_workspace_size(8, 8, 32, 8) < (80 << 20)          # decode step: room for chunks
+    assert mc.mc_attn_workspace_size(4, 3280, 64, 8) < (130 << 20)      # never more than the cap
     assert mc.mc_attn_workspace_size(1, 16, 24, 8) == 0
     assert mc.mc_attn_workspace_size(-1, 16, 32, 8) == 0
     s1 = mc.mc_attn_workspace_size(4, 1000, 32, 8)
