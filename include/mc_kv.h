@@ -216,6 +216,40 @@ mc_status mc_kv_unpack_batch(const mc_pool_desc* pool, int32_t layer_begin, int3
                              int32_t max_range_pages, const void* sendbuf /* device */,
                              void* stream);
 
+/* ---- host arithmetic of remote_send ------------------------------------------
+ * Which token ranges a sender copies, computes and sends (Sec. 3.4, the two
+ * prefix-matching cases of the attention/transfer interface).  The sender's
+ * cache holds prompt[0, sender_match), the receiver's prompt[0, receiver_match)
+ * (what its prep_recv matched, Sec. 3.2); remote_send(begin, end) has to leave
+ * prompt[begin, end) on the receiver.  With need = [max(begin, receiver_match), end):
+ *   copy    = the part of need the sender has cached: sent as it is
+ *             (Case 1, sender matched more than the receiver);
+ *   prefill = [sender_match, end) if need reaches past the sender's cache: the
+ *             sender computes every token it has not cached (attention needs the
+ *             whole context), also below need (Case 2, receiver matched more);
+ *   send    = the part of need inside the prefilled range: sent once computed.
+ * Empty ranges have begin == end.  All arguments are token counts, >= 0, and
+ * begin <= end, else MC_ERR_RANGE; plan NULL is MC_ERR_INVALID.  Host only. */
+typedef struct {
+  int32_t copy_begin, copy_end;
+  int32_t prefill_begin, prefill_end;
+  int32_t send_begin, send_end;
+} mc_send_plan;
+mc_status mc_plan_remote_send(int32_t sender_match, int32_t receiver_match, int32_t begin,
+                              int32_t end, mc_send_plan* plan /* host */);
+
+/* The "compressed form" in which prep_recv returns the addresses of the entries
+ * it reserved (Sec. 3.1): a page list as runs of consecutive page ids,
+ * runs[2 i] = first page, runs[2 i + 1] = count.  mc_addr_compress writes at
+ * most n runs (runs_out holds 2 n int32) and their number; mc_addr_expand
+ * writes the page list back (capacity = room in pages_out; MC_ERR_RANGE if the
+ * runs hold more pages, a count is <= 0 or a page id is negative).  Host only;
+ * n == 0 is legal; null pointers with n > 0 are MC_ERR_INVALID. */
+mc_status mc_addr_compress(const int32_t* pages /* host */, int32_t n,
+                           int32_t* runs_out /* host [2 n] */, int32_t* n_runs_out);
+mc_status mc_addr_expand(const int32_t* runs /* host [2 n_runs] */, int32_t n_runs,
+                         int32_t* pages_out /* host */, int32_t capacity, int32_t* n_out);
+
 /* ---- calibration: MFMA issue rate ------------------------------------------
  * Not a step of the paper's path: a measurement aid for the attention roofline
  * (the attention of Sec. 3.4 is a dense contraction on v_mfma_f32_32x32x16 with

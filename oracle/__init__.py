@@ -222,3 +222,30 @@ class Allocator:
     def give(self, pages) -> bool:
         pages = _i32(pages)
         return lib().orc_alloc_give(self._h, pages.size, _p(pages)) == 0
+
+
+# ---- host arithmetic of remote_send (paper Sec. 3.4, the two prefix-matching cases) ----
+def send_plan(sender_match: int, receiver_match: int, begin: int, end: int) -> dict:
+    """Token by token.  Token t of the prompt is on the sender if t < sender_match and on the
+    receiver if t < receiver_match.  The receiver needs t if begin <= t < end and it does not
+    have it.  A needed token the sender has is copied; if any needed token is not on the sender,
+    the sender computes every token below `end` that it lacks (attention needs the whole
+    context) and sends the needed ones among them.  Returns the three token sets as sorted
+    lists under "copy", "prefill", "send"."""
+    needed = [t for t in range(begin, end) if not t < receiver_match]
+    copy = [t for t in needed if t < sender_match]
+    must_compute = any(not t < sender_match for t in needed)
+    prefill = [t for t in range(end) if not t < sender_match] if must_compute else []
+    send = [t for t in needed if t in set(prefill)]
+    return {"copy": copy, "prefill": prefill, "send": send}
+
+
+def addr_runs(pages) -> list:
+    """Run-length form of a page list: maximal runs of consecutive ids as (first, count)."""
+    runs = []
+    for p in pages:
+        if runs and runs[-1][0] + runs[-1][1] == p:
+            runs[-1] = (runs[-1][0], runs[-1][1] + 1)
+        else:
+            runs.append((int(p), 1))
+    return runs

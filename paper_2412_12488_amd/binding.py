@@ -20,6 +20,7 @@ EXPORTS = [
     "mc_prefix_prefill_attn", "mc_kv_pack_range", "mc_kv_unpack_range",
     "mc_kv_pack_batch", "mc_kv_unpack_batch",
     "mc_mfma_probe_operand_bytes", "mc_mfma_probe",
+    "mc_plan_remote_send", "mc_addr_compress", "mc_addr_expand",
 ]
 
 
@@ -27,6 +28,11 @@ class McError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__(f"{where}: {status_string(status)}")
+
+
+class mc_send_plan(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("copy_begin", "copy_end", "prefill_begin", "prefill_end",
+                                         "send_begin", "send_end")]
 
 
 class mc_pool_desc(C.Structure):
@@ -72,6 +78,9 @@ def lib():
     L.mc_mfma_probe_operand_bytes.argtypes = []
     L.mc_mfma_probe_operand_bytes.restype = sz
     L.mc_mfma_probe.argtypes = [i32, vp, i32, i32, vp, C.POINTER(i64), vp]
+    L.mc_plan_remote_send.argtypes = [i32, i32, i32, i32, C.POINTER(mc_send_plan)]
+    L.mc_addr_compress.argtypes = [C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32)]
+    L.mc_addr_expand.argtypes = [C.POINTER(i32), i32, C.POINTER(i32), i32, C.POINTER(i32)]
     _lib = L
     return L
 
@@ -224,3 +233,31 @@ def mc_mfma_probe(dtype, operands, blocks, iters, sink, stream=None) -> int:
     _check(lib().mc_mfma_probe(dtype, _ptr(operands), blocks, iters, _ptr(sink), C.byref(flops),
                                _stream(stream)), "mc_mfma_probe")
     return int(flops.value)
+
+
+def mc_plan_remote_send(sender_match, receiver_match, begin, end) -> dict:
+    """Token ranges (begin, end) under "copy", "prefill", "send"."""
+    p = mc_send_plan()
+    _check(lib().mc_plan_remote_send(sender_match, receiver_match, begin, end, C.byref(p)),
+           "mc_plan_remote_send")
+    return {"copy": (p.copy_begin, p.copy_end), "prefill": (p.prefill_begin, p.prefill_end),
+            "send": (p.send_begin, p.send_end)}
+
+
+def mc_addr_compress(pages):
+    """Page list -> list of (first page, count) runs."""
+    n = len(pages)
+    arr, runs, nr = _i32_array(pages), (C.c_int32 * (2 * max(n, 1)))(), C.c_int32(0)
+    _check(lib().mc_addr_compress(arr, n, runs, C.byref(nr)), "mc_addr_compress")
+    return [(runs[2 * i], runs[2 * i + 1]) for i in range(nr.value)]
+
+
+def mc_addr_expand(runs, capacity=None):
+    """List of (first page, count) runs -> page list."""
+    flat = [int(x) for r in runs for x in r]
+    if capacity is None:
+        capacity = max(0, sum(max(0, int(c)) for _, c in runs))
+    out, n = (C.c_int32 * max(capacity, 1))(), C.c_int32(0)
+    _check(lib().mc_addr_expand(_i32_array(flat), len(runs), out, capacity, C.byref(n)),
+           "mc_addr_expand")
+    return [out[i] for i in range(n.value)]

@@ -1,6 +1,7 @@
 // Host-only parts of the library: status names, the page allocator behind
 // prep_recv (paper Sec. 3.1: "allocates KV cache entries for the missing
 // subsequence"), and a host check of destination page tables.
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -100,6 +101,58 @@ mc_status mc_kv_check_page_table(const int32_t* pages, int64_t n, int32_t num_pa
     if (seen[pages[i]]) return MC_ERR_ALIAS;
     seen[pages[i]] = 1;
   }
+  return MC_OK;
+}
+
+mc_status mc_plan_remote_send(int32_t sender_match, int32_t receiver_match, int32_t begin,
+                              int32_t end, mc_send_plan* plan) {
+  if (!plan) return MC_ERR_INVALID;
+  if (sender_match < 0 || receiver_match < 0 || begin < 0 || end < begin) return MC_ERR_RANGE;
+  const int32_t need_begin = std::min(std::max(begin, receiver_match), end);   // need = [., end)
+  const int32_t cached_end = std::min(sender_match, end);
+  plan->copy_begin = std::min(need_begin, cached_end);
+  plan->copy_end = cached_end;
+  if (plan->copy_begin == plan->copy_end) plan->copy_begin = plan->copy_end = need_begin;
+  const bool past_cache = need_begin < end && sender_match < end;   // need reaches uncached tokens
+  plan->prefill_begin = past_cache ? sender_match : end;
+  plan->prefill_end = end;
+  plan->send_begin = past_cache ? std::max(need_begin, sender_match) : end;
+  plan->send_end = end;
+  return MC_OK;
+}
+
+mc_status mc_addr_compress(const int32_t* pages, int32_t n, int32_t* runs_out,
+                           int32_t* n_runs_out) {
+  if (n < 0 || !n_runs_out || (n > 0 && (!pages || !runs_out))) return MC_ERR_INVALID;
+  int32_t r = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (pages[i] < 0) return MC_ERR_RANGE;
+    if (r > 0 && runs_out[2 * r - 2] + runs_out[2 * r - 1] == pages[i]) {
+      ++runs_out[2 * r - 1];
+    } else {
+      runs_out[2 * r] = pages[i];
+      runs_out[2 * r + 1] = 1;
+      ++r;
+    }
+  }
+  *n_runs_out = r;
+  return MC_OK;
+}
+
+mc_status mc_addr_expand(const int32_t* runs, int32_t n_runs, int32_t* pages_out, int32_t capacity,
+                         int32_t* n_out) {
+  if (n_runs < 0 || capacity < 0 || !n_out || (n_runs > 0 && !runs) ||
+      (capacity > 0 && !pages_out))
+    return MC_ERR_INVALID;
+  int64_t n = 0;
+  for (int32_t i = 0; i < n_runs; ++i) {
+    const int32_t first = runs[2 * i], count = runs[2 * i + 1];
+    if (first < 0 || count <= 0 || (int64_t)first + count - 1 > 0x7fffffffll) return MC_ERR_RANGE;
+    if (n + count > capacity) return MC_ERR_RANGE;
+    for (int32_t k = 0; k < count; ++k) pages_out[n + k] = first + k;
+    n += count;
+  }
+  *n_out = (int32_t)n;
   return MC_OK;
 }
 

@@ -174,3 +174,58 @@ def test_mfma_probe_validation():
     assert _status(pr, mc.MC_BF16, FAKE, 0, 1, FAKE) == mc.MC_ERR_INVALID
     assert _status(pr, mc.MC_BF16, FAKE, 4, 0, FAKE) == mc.MC_ERR_INVALID
     assert _status(pr, 7, FAKE, 4, 1, FAKE) == mc.MC_ERR_UNSUPPORTED
+
+
+def _as_range(tokens, empty_at):
+    if not tokens:
+        return (empty_at, empty_at)
+    assert tokens == list(range(tokens[0], tokens[-1] + 1))
+    return (tokens[0], tokens[-1] + 1)
+
+
+def test_plan_remote_send_matches_oracle_exhaustively():
+    hi = 10
+    for s in range(hi):
+        for r in range(hi):
+            for b in range(hi):
+                for e in range(b, hi):
+                    got = mc.mc_plan_remote_send(s, r, b, e)
+                    want = oracle.send_plan(s, r, b, e)
+                    for key in ("copy", "prefill", "send"):
+                        lo, up = got[key]
+                        assert lo <= up
+                        if want[key]:
+                            assert (lo, up) == _as_range(want[key], 0), (s, r, b, e, key, got)
+                        else:
+                            assert lo == up, (s, r, b, e, key, got)
+
+
+def test_plan_remote_send_errors():
+    for bad in [(-1, 0, 0, 1), (0, -1, 0, 1), (0, 0, -1, 1), (0, 0, 2, 1)]:
+        with pytest.raises(mc.McError) as e:
+            mc.mc_plan_remote_send(*bad)
+        assert e.value.status == mc.MC_ERR_RANGE
+    assert mc.lib().mc_plan_remote_send(1, 1, 0, 1, None) == mc.MC_ERR_INVALID
+
+
+def test_addr_compress_expand():
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(0, 40))
+        pages, p = [], int(rng.integers(0, 50))
+        for _ in range(n):
+            p = p + 1 if rng.random() < 0.6 else int(rng.integers(0, 1000))
+            pages.append(p)
+        runs = mc.mc_addr_compress(pages)
+        assert runs == oracle.addr_runs(pages)
+        assert mc.mc_addr_expand(runs) == pages
+    with pytest.raises(mc.McError) as e:
+        mc.mc_addr_compress([3, -1])
+    assert e.value.status == mc.MC_ERR_RANGE
+    for bad in ([(0, 0)], [(-1, 2)], [(2**31 - 2, 5)]):
+        with pytest.raises(mc.McError) as e:
+            mc.mc_addr_expand(bad, capacity=16)
+        assert e.value.status == mc.MC_ERR_RANGE
+    with pytest.raises(mc.McError) as e:
+        mc.mc_addr_expand([(0, 5)], capacity=4)
+    assert e.value.status == mc.MC_ERR_RANGE

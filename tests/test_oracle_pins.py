@@ -439,3 +439,41 @@ def test_config_shapes(idx):
         assert int(w.b[0]) == 7372 and w.num_q_heads == 64
     if idx == 5:
         assert list(w.n) == [16384, 32768] and w.num_layers == 32
+
+
+# ---- host arithmetic of remote_send (Sec. 3.4) ----
+def test_send_plan_case1_sender_matched_more():
+    # sender cached 300 tokens, receiver 100, request [0, 500): 100..299 exist only on the
+    # sender and go as they are; 300..499 exist nowhere: computed, then sent
+    p = oracle.send_plan(300, 100, 0, 500)
+    assert p["copy"] == list(range(100, 300))
+    assert p["prefill"] == list(range(300, 500))
+    assert p["send"] == list(range(300, 500))
+
+
+def test_send_plan_case2_receiver_matched_more():
+    # sender cached 100, receiver 300: nothing can be copied; the sender computes everything it
+    # lacks (100..499) and sends only what the receiver lacks (300..499)
+    p = oracle.send_plan(100, 300, 0, 500)
+    assert p["copy"] == []
+    assert p["prefill"] == list(range(100, 500))
+    assert p["send"] == list(range(300, 500))
+
+
+def test_send_plan_degenerate_cases():
+    assert oracle.send_plan(500, 0, 0, 500) == {"copy": list(range(500)), "prefill": [], "send": []}
+    assert oracle.send_plan(0, 500, 0, 500) == {"copy": [], "prefill": [], "send": []}
+    assert oracle.send_plan(0, 0, 0, 0) == {"copy": [], "prefill": [], "send": []}
+    # a request that starts above what the receiver has: the gap below begin is not sent
+    p = oracle.send_plan(50, 10, 40, 60)
+    assert p["copy"] == list(range(40, 50)) and p["send"] == list(range(50, 60))
+    # everything the receiver gets is exactly what it lacked in [begin, end), once
+    for s, r, b, e in [(7, 3, 2, 11), (3, 7, 0, 11), (5, 5, 5, 9), (20, 1, 4, 9)]:
+        p = oracle.send_plan(s, r, b, e)
+        assert sorted(p["copy"] + p["send"]) == [t for t in range(b, e) if t >= r]
+
+
+def test_addr_runs():
+    assert oracle.addr_runs([]) == []
+    assert oracle.addr_runs([5, 6, 7, 9, 10, 3, 4, 4]) == [(5, 3), (9, 2), (3, 2), (4, 1)]
+    assert oracle.addr_runs([2, 1, 0]) == [(2, 1), (1, 1), (0, 1)]
