@@ -106,12 +106,15 @@ def attention_only(name, iters, values="normal"):
     ms = e0.elapsed_time(e1) / iters
     fl = w.useful_flops()
     alg_bytes = 2 * tq * Hq * 256 + tq * Hq * 4 + int(np.sum(w.n)) * w.token_bytes
-    print(json.dumps({"workload": w.name, "values": values, "new_tokens": tq,
-                      "kv_tokens": int(np.sum(w.n)),
-                      "algorithmic_GBps": round(alg_bytes / ms / 1e6, 1),
-                      "useful_flops": fl, "ms": round(ms, 4),
-                      "TFLOPs": round(fl / ms / 1e9, 1),
-                      "frac_of_mfma_peak": round(fl / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}))
+    res = {"workload": w.name, "values": values, "new_tokens": tq,
+           "kv_tokens": int(np.sum(w.n)),
+           "algorithmic_GBps": round(alg_bytes / ms / 1e6, 1),
+           "useful_flops": fl, "ms": round(ms, 4),
+           "TFLOPs": round(fl / ms / 1e9, 1),
+           "frac_of_mfma_peak": round(fl / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}
+    del pool, q, out, lse, ws
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -147,7 +150,8 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     if args.attention_only:
-        attention_only(args.attention_only, max(1, min(args.steps, 20)), args.values)
+        print(json.dumps(attention_only(args.attention_only, max(1, min(args.steps, 20)),
+                                        args.values)))
         return
 
     def up(a):
@@ -290,6 +294,17 @@ def main():
                      "normal_operands_TFLOPs": mfma_rate(ops_normal)}
     del ops_const, ops_normal
 
+    # ---- the attention call on the paper's Table-2 shapes and on decode steps (one new token
+    #      per sequence, alone and fused with a prefill range): the planner cuts their KV
+    #      ranges into chunks; decode is bound by HBM, so its figure is algorithmic GB/s ----
+    other = {}
+    if not args.no_copy_sweep:
+        for name in ("paper-500-over-500", "paper-500-over-2500", "paper-500-over-4500",
+                     "decode-64", "decode-256", "decode-64-plus-prefill"):
+            r = attention_only(name, 10)
+            other[name] = {"ms": r["ms"], "TFLOPs": r["TFLOPs"],
+                           "algorithmic_GBps": r["algorithmic_GBps"]}
+
     # ---- copies, each alone: this workload, then the long-context transfer size ----
     copy = {}
     kv_bytes = int(np.sum(w.n)) * w.token_bytes
@@ -402,6 +417,7 @@ def main():
             "traffic": MEASURED_TRAFFIC["pack_4GiB_bytes"],
             "algorithmic_bytes": 2 * int(copy["long_context"]["payload_GiB"] * 2**30)},
         "copy": copy,
+        "attention_other_workloads": other or None,
         "cpu_baseline": cpu,
     }
     print(json.dumps(result))

@@ -74,6 +74,7 @@ struct MergeRec {
   int32_t ntok, nsplit, part;
 };
 
+constexpr int kCuTilesInLds = 2048;
 constexpr int kMinChunkTiles = 8;     // never cut a KV range into pieces shorter than 512 keys
 constexpr int kRoundsWanted = 4;      // cut only while the launch has fewer items than 4 per slot
 
@@ -129,21 +130,28 @@ struct PlanArgs {
   int32_t hkv, slots;   // kv heads; workgroups the GPU runs at a time
 };
 
-// Block-wide exclusive scan of one value per thread (kPlanThreads threads).
+// Block-wide exclusive scan of one value per thread (kPlanThreads threads): a shuffle scan
+// inside each wavefront, the 16 wavefront totals through LDS, two barriers in all.
 __device__ int block_exclusive_scan(int v, int* lds, int* total) {
-  const int t = threadIdx.x;
-  lds[t] = v;
-  __syncthreads();
-  for (int off = 1; off < kPlanThreads; off <<= 1) {
-    int add = t >= off ? lds[t - off] : 0;
-    __syncthreads();
-    lds[t] += add;
-    __syncthreads();
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
   }
-  const int incl = lds[t];
-  *total = lds[kPlanThreads - 1];
+  __syncthreads();               // earlier readers of lds are done
+  if (lane == 63) lds[wave] = incl;
   __syncthreads();
-  return incl - v;
+  int before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kPlanThreads / 64; ++w) {
+    const int x = lds[w];
+    if (w < wave) before += x;
+    all += x;
+  }
+  *total = all;
+  return before + incl - v;
 }
 
 // One workgroup.  Validates the ragged-batch arrays, cuts every sequence's new range into q
@@ -155,10 +163,21 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   __shared__ int scan[kPlanThreads];
   __shared__ int hist[kBuckets];
   __shared__ int s_err, s_maxcost, s_chunk, s_part_tokens;
+  // per-sequence arrays of batches that fit: the searches and tile look-ups below stay in LDS
+  __shared__ int s_cu[kCuTilesInLds + 1], s_cuq[kCuTilesInLds + 1], s_beg[kCuTilesInLds],
+      s_cup[kCuTilesInLds + 1];
   __shared__ unsigned long long s_cost;
   const int t = threadIdx.x;
   if (t == 0) { s_err = 0; s_maxcost = 1; s_cost = 0; s_chunk = 0; s_part_tokens = 0; }
   for (int i = t; i < kBuckets; i += kPlanThreads) hist[i] = 0;
+  const bool cu_in_lds = a.batch <= kCuTilesInLds;
+  if (cu_in_lds) {
+    for (int i = t; i <= a.batch; i += kPlanThreads) {
+      s_cuq[i] = a.cu_q[i];
+      s_cup[i] = a.cu_pages[i];
+      if (i < a.batch) s_beg[i] = a.begin[i];
+    }
+  }
   __syncthreads();
 
   // 1. validate, count tiles per sequence (contiguous chunk of sequences per thread)
@@ -183,14 +202,50 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
     return;
   }
-  // 2. page ids of every needed table entry (one wavefront per sequence at a time)
-  for (int s = t >> 6; s < a.batch; s += kPlanThreads >> 6) {
+  // 2. page ids of every needed table entry.  Batches whose offsets sit in LDS: a wavefront
+  //    takes four sequences per trip and has up to 32 loads per lane in flight (the loop is
+  //    bound by memory latency); entries beyond the first 512 of a sequence follow one
+  //    sequence at a time.
+  if (cu_in_lds) {
+    for (int s4 = (t >> 6) * 4; s4 < a.batch; s4 += (kPlanThreads >> 6) * 4) {
+      int32_t pg[4][8];
+      int need[4], p0[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int s = s4 + k;
+        const int q = s < a.batch ? s_cuq[s + 1] - s_cuq[s] : 0;
+        need[k] = q > 0 ? (s_beg[s] + q + kPage - 1) / kPage : 0;
+        p0[k] = s < a.batch ? s_cup[s] : 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int i = (t & 63) + 64 * u;
+          pg[k][u] = i < need[k] ? a.page_table[p0[k] + i] : 0;
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (pg[k][u] < 0 || pg[k][u] >= a.num_pages) err = 1;
+        for (int i = 512 + (t & 63); i < need[k]; i += 64) {
+          const int32_t x = a.page_table[p0[k] + i];
+          if (x < 0 || x >= a.num_pages) err = 1;
+        }
+      }
+    }
+  }
+  for (int s = t >> 6; !cu_in_lds && s < a.batch; s += kPlanThreads >> 6) {
     const int q = a.cu_q[s + 1] - a.cu_q[s];
     if (q == 0) continue;
     const int need = (a.begin[s] + q + kPage - 1) / kPage, p0 = a.cu_pages[s];
-    for (int i = t & 63; i < need; i += 64) {
-      const int32_t pg = a.page_table[p0 + i];
-      if (pg < 0 || pg >= a.num_pages) err = 1;
+    // eight independent loads per lane and trip: the loop is bound by memory latency
+    for (int i = t & 63; i < need; i += 64 * 8) {
+      int32_t pg[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) pg[u] = i + 64 * u < need ? a.page_table[p0 + i + 64 * u] : 0;
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (pg[u] < 0 || pg[u] >= a.num_pages) err = 1;
     }
   }
   if (err) atomicOr(&s_err, 1);
@@ -205,6 +260,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   if (t == 0) a.cu_tiles[a.batch] = total_tiles;
   __threadfence_block();
   __syncthreads();
+  if (cu_in_lds) {
+    for (int i = t; i <= a.batch; i += kPlanThreads) s_cu[i] = a.cu_tiles[i];
+    __syncthreads();
+  }
   if (s_err || total_tiles > a.max_tiles) {
     if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
     return;
@@ -217,12 +276,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     int lo = 0, hi = a.batch;
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
-      if (a.cu_tiles[mid] <= i) lo = mid; else hi = mid;
+      if ((cu_in_lds ? s_cu[mid] : a.cu_tiles[mid]) <= i) lo = mid; else hi = mid;
     }
     Tile x;
     x.s = lo;
-    x.row0 = (i - a.cu_tiles[lo]) * a.tile_tokens;
-    const int q = a.cu_q[lo + 1] - a.cu_q[lo], b = a.begin[lo];
+    x.row0 = (i - (cu_in_lds ? s_cu[lo] : a.cu_tiles[lo])) * a.tile_tokens;
+    const int q = cu_in_lds ? s_cuq[lo + 1] - s_cuq[lo] : a.cu_q[lo + 1] - a.cu_q[lo];
+    const int b = cu_in_lds ? s_beg[lo] : a.begin[lo];
     x.ntok = min(a.tile_tokens, q - x.row0);
     x.T = (b + x.row0 + x.ntok + kBN - 1) / kBN;
     x.dmax = ((b + x.row0) / kBN) & ~1;
@@ -300,7 +360,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     const int ns = splits_of(x, L);
     if (ns > 1) {
       MergeRec m;
-      m.q_row = a.cu_q[x.s] + x.row0;
+      m.q_row = (cu_in_lds ? s_cuq[x.s] : a.cu_q[x.s]) + x.row0;
       m.ntok = x.ntok;
       m.nsplit = ns;
       m.part = part_off;
@@ -779,9 +839,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 }
 
 // Combines the chunks of every q tile whose KV range was cut: with L_c the chunk LSEs,
-// LSE = log sum_c exp(L_c) and O = sum_c exp(L_c - LSE) O_c.  One workgroup per (cut tile,
-// token), one wavefront per q head at a time, two d per lane; a chunk's loads do not depend on
-// another chunk's, so they are all in flight together.
+// LSE = log sum_c exp(L_c) and O = sum_c exp(L_c - LSE) O_c.  A fixed grid walks the (cut tile,
+// token, four q heads) triples - the host does not know how many tiles were cut, usually none -
+// one wavefront per q head, two d per lane; a chunk's loads do not depend on another chunk's,
+// so they are all in flight together.
 struct MergeArgs {
   const PlanHeader* hdr;
   const MergeRec* merges;
@@ -789,18 +850,22 @@ struct MergeArgs {
   const float* part_o;
   char* out;
   float* lse;
-  int32_t hq;
+  int32_t hq, tile_tokens;
 };
 
 template <typename T>
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
-  if (a.hdr->magic != kPlanMagic || (int)blockIdx.x >= a.hdr->num_merges) return;
-  const MergeRec m = a.merges[blockIdx.x];
-  const int tt = blockIdx.y;
-  if (tt >= m.ntok) return;
+  if (a.hdr->magic != kPlanMagic) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int head_groups = (a.hq + 3) / 4;
+  const int per_tile = a.tile_tokens * head_groups;
+  const int64_t total = (int64_t)a.hdr->num_merges * per_tile;   // usually 0: nothing was cut
   typedef float f32x2 __attribute__((ext_vector_type(2)));
-  for (int h = wave; h < a.hq; h += 4) {
+  for (int64_t wk = blockIdx.x; wk < total; wk += gridDim.x) {
+    const MergeRec m = a.merges[wk / per_tile];
+    const int rest = (int)(wk % per_tile);
+    const int tt = rest / head_groups, h = rest % head_groups * 4 + wave;
+    if (tt >= m.ntok || h >= a.hq) continue;
     float mx = -INFINITY;
     for (int c = 0; c < m.nsplit; ++c)
       mx = fmaxf(mx, a.part_lse[(int64_t)(m.part + c * m.ntok + tt) * a.hq + h]);
@@ -1000,10 +1065,12 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
   m.out = a.out;
   m.lse = a.lse;
   m.hq = num_q_heads;
+  m.tile_tokens = kBM / G;
+  const dim3 mgrid(4 * slots);
   if (pool->dtype == MC_F16)
-    hipLaunchKernelGGL(merge_kernel<_Float16>, dim3(w.max_tiles, kBM / G), dim3(256), 0, hs, m);
+    hipLaunchKernelGGL(merge_kernel<_Float16>, mgrid, dim3(256), 0, hs, m);
   else
-    hipLaunchKernelGGL(merge_kernel<__bf16>, dim3(w.max_tiles, kBM / G), dim3(256), 0, hs, m);
+    hipLaunchKernelGGL(merge_kernel<__bf16>, mgrid, dim3(256), 0, hs, m);
   return mc::launch_status();
 }
 
