@@ -77,6 +77,9 @@ struct MergeRec {
 constexpr int kCuTilesInLds = 2048;
 constexpr int kMinChunkTiles = 8;     // never cut a KV range into pieces shorter than 512 keys
 constexpr int kRoundsWanted = 4;      // cut only while the launch has fewer items than 4 per slot
+// ... and then aim for about one item per slot: measured best on decode batches and on 500-token
+// ranges over long contexts (more chunks mean more partial rows to write and merge)
+constexpr int kItemsPerSlot = 1;
 
 struct WorkspaceLayout {
   size_t cu_tiles, items, merges, part_lse, part_o, total;
@@ -292,16 +295,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   auto splits_of = [&](const Tile& x, int L) { return L > 0 ? x.dmax / L + 1 : 1; };
 
   // 4. chunk length.  No cutting when the q tiles alone give the GPU kRoundsWanted rounds of
-  //    work; otherwise aim for that many items, never below kMinChunkTiles, and double the
-  //    length until the partial rows fit the workspace.
+  //    work; otherwise a length that would make about kItemsPerSlot items per slot, never
+  //    below kMinChunkTiles, doubled until the partial rows fit the workspace.
   int L = 0;
   if ((int64_t)total_tiles * a.hkv < (int64_t)kRoundsWanted * a.slots) {
     unsigned long long cost = 0;
     for (int i = t; i < total_tiles; i += kPlanThreads) cost += locate(i).T;
     atomicAdd(&s_cost, cost);
     __syncthreads();
-    const long long want = (long long)((s_cost * a.hkv + (unsigned long long)kRoundsWanted * a.slots - 1) /
-                                       ((unsigned long long)kRoundsWanted * a.slots));
+    const long long want = (long long)((s_cost * a.hkv + (unsigned long long)kItemsPerSlot * a.slots - 1) /
+                                       ((unsigned long long)kItemsPerSlot * a.slots));
     L = want < kMinChunkTiles ? kMinChunkTiles : want > (1 << 28) ? (1 << 28) : (int)want;
     L = (L + 1) & ~1;
     for (;;) {
