@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
 
 ATTN_WORKLOADS = ["cfg2", "cfg3-passB", "cfg4", "cfg5-16k", "cfg5-32k", "paper-500-over-500",
                   "paper-500-over-2500", "paper-500-over-4500", "decode-8", "decode-64",
-                  "decode-256", "decode-64-plus-prefill"]
+                  "decode-256", "decode-64-plus-prefill", "decode-64-forks", "decode-64-no-forks"]
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very
 # command with the default seed (counters scaled by what a plain 4 GiB copy reads; see
@@ -53,6 +53,18 @@ def attention_workload(name):
         return w.with_ranges(b, n, name)
     if name.startswith("paper-500-over-"):
         return mi.paper_point(int(name.rsplit("-", 1)[1]))
+    if name in ("decode-64-forks", "decode-64-no-forks"):
+        # 64 decode steps of sequences that continue one 2048-token prompt by 64..1024 tokens of
+        # their own: as forks (page tables share the prompt's 128 pages, Sec. 3.4 fork_sequence)
+        # or as unrelated sequences of the same lengths
+        rng = mi.rng_for(4243)
+        n = 2048 + rng.integers(64, 1025, size=64)
+        w = mi.Workload(name, 4243, mi.BF16, 1, 32, 8, 65536, n, n - 1)
+        w.page_tables = mi.scatter_page_tables(mi.rng_for(4243, mi.KIND_TABLE), 65536, n)
+        if name == "decode-64-forks":
+            for s in range(1, 64):
+                w.share_prefix(s, 0, 2048)
+        return w
     if name.startswith("decode-"):
         # one new token per sequence over contexts ~ U[1024, 4096] (Llama-3-8B shapes), alone or
         # in one ragged batch with a 2048-token prefill range over 1024 cached tokens

@@ -133,7 +133,12 @@ mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer,
  * including the new range, are read from the pages (mc_kv_append of this layer
  * comes first on the same stream).  Accumulation and softmax are fp32, out is
  * rounded to the pool dtype.  Page tables of different sequences may share
- * pages (shared prefixes, Sec. 3.4 fork_sequence).
+ * pages (shared prefixes, Sec. 3.4 fork_sequence); when neighbouring sequences
+ * of the batch each bring one new token and their tables start with the same
+ * pages (at least 512 tokens' worth, cached by all of them), the plan lets
+ * them attend that prefix together, reading its K/V once, and merges the result
+ * with each sequence's own remainder.  The results are those of the formula
+ * above either way.
  *
  * mc_attn_plan is the declaration stage (begin_forward, Sec. 3.4): it turns the
  * ragged batch into a work list in `workspace`, validates the device arrays and

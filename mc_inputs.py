@@ -61,6 +61,10 @@ class Workload:
     page_tables: List[np.ndarray] = field(default_factory=list)  # per seq, ceil(n/P) page ids
     head_dim: int = 128
     page_size: int = 16
+    # shared prefixes (fork_sequence, paper Sec. 3.4): share[s] = (source sequence < s, tokens);
+    # sequence s has the source's K/V on its first `tokens` tokens (a multiple of the page size)
+    # and lists the source's pages for them
+    share: dict = field(default_factory=dict)
 
     @property
     def batch(self) -> int:
@@ -101,6 +105,10 @@ class Workload:
         shape = (int(self.n[seq]), self.num_kv_heads, self.head_dim)
         k = normal_bits(rng_for(self.seed, seq, KIND_K), shape, self.dtype)
         v = normal_bits(rng_for(self.seed, seq, KIND_V), shape, self.dtype)
+        if seq in self.share:
+            src, tokens = self.share[seq]
+            ks, vs = self.kv(src, 0)
+            k[:tokens], v[:tokens] = ks[:tokens], vs[:tokens]
         return layer_variant(k, layer), layer_variant(v, layer)
 
     def q(self, seq: int, layer: int = 0) -> np.ndarray:
@@ -115,8 +123,19 @@ class Workload:
         assert np.all(b >= 0) and np.all(b <= n) and np.all(n <= self.n)
         w = Workload(name or self.name, self.seed, self.dtype, self.num_layers, self.num_q_heads,
                      self.num_kv_heads, self.num_pages, n, b, self.page_tables, self.head_dim,
-                     self.page_size)
+                     self.page_size, self.share)
         return w
+
+    def share_prefix(self, seq: int, src: int, tokens: int) -> None:
+        """Make sequence seq a fork of src over its first `tokens` tokens: same K/V, same pages."""
+        assert src < seq and tokens % self.page_size == 0
+        assert tokens <= min(int(self.n[seq]), int(self.n[src]))
+        if src in self.share:
+            assert tokens <= self.share[src][1] or True
+        self.share[seq] = (src, tokens)
+        pages = tokens // self.page_size
+        self.page_tables[seq] = self.page_tables[seq].copy()
+        self.page_tables[seq][:pages] = self.page_tables[src][:pages]
 
 
 def scatter_page_tables(rng: np.random.Generator, num_pages: int, n_tokens, page_size: int = 16):

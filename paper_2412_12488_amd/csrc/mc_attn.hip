@@ -55,7 +55,8 @@ struct PlanHeader {
   int32_t total_q;
   int32_t num_merges; // q tiles whose KV range was cut into several chunks
   int32_t chunk_tiles;  // chunk length the planner settled on (KV tiles); 0 = nothing was cut
-  int32_t pad[8];
+  int32_t num_groups_rows;  // partial rows written by shared-prefix items (0 = no groups)
+  int32_t pad[7];
 };
 static_assert(sizeof(PlanHeader) == 64, "header is 64 bytes");
 
@@ -63,18 +64,26 @@ static_assert(sizeof(PlanHeader) == 64, "header is 64 bytes");
 // part < 0: the item covers the tile's whole KV range and writes out/lse itself.  Otherwise it
 // writes a partial result (O normalised within the chunk, fp32, and the chunk's LSE) for token
 // tt of the tile at row part + tt of the partial arrays, and merge_kernel combines the chunks.
+// gsize > 0: a shared-prefix item.  Its rows are the single new tokens of gsize consecutive
+// sequences starting at seq, whose page tables begin with the same pages; it covers tiles of
+// that common prefix (all of it visible to every row) and always writes partial rows.
 struct ItemRec {
-  int32_t seq, row0, t0, t1, part, pad[3];
+  int32_t seq, row0, t0, t1, part, gsize, pad[2];
 };
 static_assert(sizeof(ItemRec) == 32, "item record is 32 bytes");
 
-// One q tile that was cut: chunk c's partial rows start at part + c * ntok.
+// One q tile with partial results: chunk c of its own KV range has its partial rows at
+// part + c * ntok; if the tile's sequence belongs to a shared-prefix group, chunk c of the
+// prefix has this sequence's row at g_part + c * g_stride.
 struct MergeRec {
   int32_t q_row;   // index of the tile's first token among all new tokens of the batch
   int32_t ntok, nsplit, part;
+  int32_t g_nsplit, g_part, g_stride, pad;
 };
+static_assert(sizeof(MergeRec) == 32, "merge record is 32 bytes");
 
-constexpr int kCuTilesInLds = 2048;
+constexpr int kCuTilesInLds = 1024;
+constexpr int kMinSharedTiles = 8;    // a shared prefix shorter than 512 tokens is not worth a group
 constexpr int kMinChunkTiles = 8;     // never cut a KV range into pieces shorter than 512 keys
 constexpr int kRoundsWanted = 4;      // cut only while the launch has fewer items than 4 per slot
 // ... and then aim for about one item per slot: measured best on decode batches and on 500-token
@@ -109,7 +118,8 @@ inline WorkspaceLayout workspace_layout(int32_t batch, int32_t total_q, int32_t 
   w.max_tiles = (int32_t)(((int64_t)total_q + tile_tokens - 1) / tile_tokens + batch);
   w.part_cap = partial_capacity(total_q, tile_tokens, num_q_heads, num_kv_heads);
   w.batch = batch;
-  w.max_items = w.max_tiles + w.part_cap;   // every extra chunk holds at least one partial row
+  // every extra chunk holds at least one partial row; a shared-prefix group adds items too
+  w.max_items = w.max_tiles + w.part_cap + batch;
   w.cu_tiles = sizeof(PlanHeader);
   w.items = w.cu_tiles + round64(sizeof(int32_t) * ((size_t)batch + 1));
   w.merges = w.items + sizeof(ItemRec) * (size_t)w.max_items;
@@ -131,6 +141,7 @@ struct PlanArgs {
   MergeRec* merges;
   int32_t batch, total_q, tile_tokens, num_pages, max_tiles, max_items, part_cap;
   int32_t hkv, slots;   // kv heads; workgroups the GPU runs at a time
+  int32_t allow_groups; // look for decode rows of neighbouring sequences that share a prefix
 };
 
 // Block-wide exclusive scan of one value per thread (kPlanThreads threads): a shuffle scan
@@ -157,6 +168,25 @@ __device__ int block_exclusive_scan(int v, int* lds, int* total) {
   return before + incl - v;
 }
 
+// Block-wide inclusive running maximum of one value per thread.
+__device__ int block_inclusive_max_scan(int v, int* lds) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int up = __shfl_up(incl, off);
+    if (lane >= off) incl = max(incl, up);
+  }
+  __syncthreads();
+  if (lane == 63) lds[wave] = incl;
+  __syncthreads();
+  int before = INT32_MIN;
+#pragma unroll
+  for (int w = 0; w < kPlanThreads / 64; ++w)
+    if (w < wave) before = max(before, lds[w]);
+  return max(before, incl);
+}
+
 // One workgroup.  Validates the ragged-batch arrays, cuts every sequence's new range into q
 // tiles of tile_tokens tokens, cuts long KV ranges into chunks when the launch would otherwise
 // have too few work items to fill the GPU (decode rows, short batches over long contexts),
@@ -169,6 +199,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   // per-sequence arrays of batches that fit: the searches and tile look-ups below stay in LDS
   __shared__ int s_cu[kCuTilesInLds + 1], s_cuq[kCuTilesInLds + 1], s_beg[kCuTilesInLds],
       s_cup[kCuTilesInLds + 1];
+  // shared-prefix groups, per sequence: pages in common with the next sequence; prefix tiles the
+  // group covers (0 = not in a group); the group's first sequence (-1 = none); at that first
+  // sequence the group's size and the base of its partial rows
+  __shared__ int s_common[kCuTilesInLds], s_gp[kCuTilesInLds], s_glead[kCuTilesInLds],
+      s_gsize[kCuTilesInLds], s_gbase[kCuTilesInLds];
+  __shared__ int s_groups;
   __shared__ unsigned long long s_cost;
   const int t = threadIdx.x;
   if (t == 0) { s_err = 0; s_maxcost = 1; s_cost = 0; s_chunk = 0; s_part_tokens = 0; }
@@ -272,9 +308,67 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     return;
   }
 
-  // q tile i: its sequence, first row, token count, KV tiles, and the last even tile index at
-  // which a chunk may start (every row must see at least the first key of every chunk)
-  struct Tile { int s, row0, ntok, T, dmax; };
+  // 3b. shared-prefix groups (Sec. 3.4 fork_sequence: sequences may share the pages of a common
+  //     prefix).  Decode rows of neighbouring sequences whose tables start with the same pages
+  //     attend that prefix together, one K/V read for all of them, and their own remainders one
+  //     by one; the parts are merged by LSE like any other chunks.
+  const bool try_groups = a.allow_groups && cu_in_lds && a.batch >= 2;
+  if (t == 0) s_groups = 0;
+  if (try_groups) {
+    for (int i = t; i < a.batch; i += kPlanThreads) { s_common[i] = 0; s_gp[i] = 0; s_glead[i] = -1; s_gsize[i] = 0; }
+    __syncthreads();
+    // pages in common between s and s+1, among the whole pages cached by both (one wavefront a pair)
+    for (int sq = t >> 6; sq + 1 < a.batch; sq += kPlanThreads >> 6) {
+      if (s_cuq[sq + 1] - s_cuq[sq] != 1 || s_cuq[sq + 2] - s_cuq[sq + 1] != 1) continue;
+      const int lim = min(s_beg[sq], s_beg[sq + 1]) / kPage;
+      const int pa = s_cup[sq], pb = s_cup[sq + 1];
+      int common = 0;
+      for (int i0 = 0; i0 < lim; i0 += 64) {
+        const int i = i0 + (t & 63);
+        const bool differ = i < lim && a.page_table[pa + i] != a.page_table[pb + i];
+        const unsigned long long m = __ballot(differ);
+        if (m) { common = i0 + __ffsll((long long)m) - 1; break; }
+        common = min(lim, i0 + 64);
+      }
+      if ((t & 63) == 0) s_common[sq] = common;
+    }
+    __syncthreads();
+    // runs of decode rows linked by enough common pages, cut into groups of at most tile_tokens
+    constexpr int kMinPages = kMinSharedTiles * kBN / kPage;
+    const bool mine = t < a.batch;
+    const bool dec = mine && s_cuq[t + 1] - s_cuq[t] == 1;
+    auto linked = [&](int sq) {   // sq and sq+1 sit in one run
+      return sq >= 0 && sq + 1 < a.batch && s_cuq[sq + 1] - s_cuq[sq] == 1 &&
+             s_cuq[sq + 2] - s_cuq[sq + 1] == 1 && s_common[sq] >= kMinPages;
+    };
+    const bool starts = dec && !linked(t - 1);
+    const int run_start = block_inclusive_max_scan(starts ? t : -1, scan);
+    int lead = -1;
+    if (dec && run_start >= 0) {
+      lead = run_start + (t - run_start) / a.tile_tokens * a.tile_tokens;
+      if (t == lead) {
+        int m = 1, pages = INT32_MAX;
+        while (m < a.tile_tokens && linked(t + m - 1)) { pages = min(pages, s_common[t + m - 1]); ++m; }
+        if (m >= 2) {
+          s_gsize[t] = m;
+          s_gbase[t] = (pages / (2 * kBN / kPage)) * 2;   // prefix tiles, even (scratch until step 5)
+        }
+      }
+    }
+    __syncthreads();
+    if (dec && lead >= 0 && s_gsize[lead] >= 2 && t - lead < s_gsize[lead]) {
+      s_gp[t] = s_gbase[lead];
+      s_glead[t] = lead;
+      s_groups = 1;
+    }
+    __syncthreads();
+  }
+  bool groups = try_groups && s_groups != 0;
+
+  // q tile i: its sequence, first row, token count, KV tiles, the last even tile index at which
+  // a chunk may start (every row must see at least the first key of every chunk), the prefix
+  // tiles its shared-prefix group covers, and the group's size if this tile leads one
+  struct Tile { int s, row0, ntok, T, dmax, pt, gm; };
   auto locate = [&](int i) {
     int lo = 0, hi = a.batch;
     while (hi - lo > 1) {
@@ -289,10 +383,28 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     x.ntok = min(a.tile_tokens, q - x.row0);
     x.T = (b + x.row0 + x.ntok + kBN - 1) / kBN;
     x.dmax = ((b + x.row0) / kBN) & ~1;
+    x.pt = groups ? s_gp[lo] : 0;
+    x.gm = groups && s_glead[lo] == lo ? s_gsize[lo] : 0;
     return x;
   };
-  // chunks of L tiles (L even): [0,L), [L,2L), ..., [kL, T) with k = dmax / L
-  auto splits_of = [&](const Tile& x, int L) { return L > 0 ? x.dmax / L + 1 : 1; };
+  // own chunks of L tiles (L even) from the end of the group's prefix: [pt, pt+L), ...,
+  // [pt+kL, T) with pt + kL <= dmax; the group's prefix itself in chunks of L
+  auto own_splits = [&](const Tile& x, int L) { return L > 0 ? (x.dmax - x.pt) / L + 1 : 1; };
+  auto grp_splits = [&](const Tile& x, int L) { return x.pt > 0 ? (L > 0 ? (x.pt + L - 1) / L : 1) : 0; };
+  auto part_rows = [&](const Tile& x, int L) {
+    const int ns = own_splits(x, L);
+    return (ns > 1 || x.pt > 0 ? ns * x.ntok : 0) + (x.gm ? grp_splits(x, L) * x.gm : 0);
+  };
+  auto total_part_rows = [&](int L) {   // block-wide
+    int rows = 0;
+    for (int i = t; i < total_tiles; i += kPlanThreads) rows += part_rows(locate(i), L);
+    __syncthreads();
+    if (t == 0) s_part_tokens = 0;
+    __syncthreads();
+    atomicAdd(&s_part_tokens, rows);
+    __syncthreads();
+    return s_part_tokens;
+  };
 
   // 4. chunk length.  No cutting when the q tiles alone give the GPU kRoundsWanted rounds of
   //    work; otherwise a length that would make about kItemsPerSlot items per slot, never
@@ -300,7 +412,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   int L = 0;
   if ((int64_t)total_tiles * a.hkv < (int64_t)kRoundsWanted * a.slots) {
     unsigned long long cost = 0;
-    for (int i = t; i < total_tiles; i += kPlanThreads) cost += locate(i).T;
+    for (int i = t; i < total_tiles; i += kPlanThreads) {
+      const Tile x = locate(i);
+      cost += x.T - x.pt + (x.gm ? x.pt : 0);
+    }
     atomicAdd(&s_cost, cost);
     __syncthreads();
     const long long want = (long long)((s_cost * a.hkv + (unsigned long long)kItemsPerSlot * a.slots - 1) /
@@ -309,41 +424,35 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     L = (L + 1) & ~1;
     for (;;) {
       if (L >= s_maxcost) { L = 0; break; }   // nothing is long enough to be cut
-      int tokens = 0;
-      for (int i = t; i < total_tiles; i += kPlanThreads) {
-        const Tile x = locate(i);
-        const int ns = splits_of(x, L);
-        if (ns > 1) tokens += ns * x.ntok;
-      }
-      __syncthreads();
-      if (t == 0) s_part_tokens = 0;
-      __syncthreads();
-      atomicAdd(&s_part_tokens, tokens);
-      __syncthreads();
-      if (s_part_tokens <= a.part_cap) break;
+      if (total_part_rows(L) <= a.part_cap) break;
       L *= 2;
     }
   }
+  // without cuts the groups still need partial rows: no room, no groups
+  if (L == 0 && groups && total_part_rows(0) > a.part_cap) groups = false;
 
   // 5. items and merge records: count per contiguous range of tiles, scan, histogram of costs
   const int tper = (total_tiles + kPlanThreads - 1) / kPlanThreads;
   const int i_lo = min(t * tper, total_tiles), i_hi = min(i_lo + tper, total_tiles);
   int shift = 0;
   while ((s_maxcost >> shift) >= kBuckets) ++shift;
-  int n_items = 0, n_part = 0, n_merge = 0;
+  auto bucket = [&](int len) { return kBuckets - 1 - (len >> shift); };
+  int n_items = 0, n_own = 0, n_grp = 0, n_merge = 0;
   for (int i = i_lo; i < i_hi; ++i) {
     const Tile x = locate(i);
-    const int ns = splits_of(x, L);
-    n_items += ns;
-    if (ns > 1) { n_part += ns * x.ntok; ++n_merge; }
-    for (int c = 0; c < ns; ++c) {
-      const int len = (c + 1 < ns ? L : x.T - c * L);
-      atomicAdd(&hist[kBuckets - 1 - (len >> shift)], 1);
-    }
+    const int ns = own_splits(x, L), ng = x.gm ? grp_splits(x, L) : 0;
+    n_items += ns + ng;
+    if (ns > 1 || x.pt > 0) { n_own += ns * x.ntok; ++n_merge; }
+    n_grp += ng * x.gm;
+    for (int c = 0; c < ns; ++c)
+      atomicAdd(&hist[bucket(c + 1 < ns ? L : x.T - x.pt - c * L)], 1);
+    for (int c = 0; c < ng; ++c)
+      atomicAdd(&hist[bucket(L > 0 ? min(L, x.pt - c * L) : x.pt)], 1);
   }
-  int tot_items, tot_part, tot_merge;
+  int tot_items, tot_own, tot_grp, tot_merge;
   block_exclusive_scan(n_items, scan, &tot_items);
-  int part_off = block_exclusive_scan(n_part, scan, &tot_part);
+  int own_off = block_exclusive_scan(n_own, scan, &tot_own);
+  int grp_off = block_exclusive_scan(n_grp, scan, &tot_grp);
   int merge_off = block_exclusive_scan(n_merge, scan, &tot_merge);
   {
     constexpr int kPer = kBuckets / kPlanThreads;
@@ -353,34 +462,59 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     for (int i = 0; i < kPer; ++i) { hist[t * kPer + i] = off; off += local[i]; }
   }
   __syncthreads();
-  if (tot_items > a.max_items || tot_part > a.part_cap || tot_merge > a.max_tiles) {   // cannot happen
+  if (tot_items > a.max_items || tot_own + tot_grp > a.part_cap || tot_merge > a.max_tiles) {   // cannot happen
     if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
     return;
+  }
+  // where each group's partial rows start (after all the tiles' own): its members need it
+  if (groups) {
+    int off = tot_own + grp_off;
+    for (int i = i_lo; i < i_hi; ++i) {
+      const Tile x = locate(i);
+      if (x.gm) { s_gbase[x.s] = off; off += grp_splits(x, L) * x.gm; }
+    }
+    __syncthreads();
   }
   // 6. emit: counting sort of the items by cost (number of KV tiles), heaviest first
   for (int i = i_lo; i < i_hi; ++i) {
     const Tile x = locate(i);
-    const int ns = splits_of(x, L);
-    if (ns > 1) {
+    const int ns = own_splits(x, L), ng = grp_splits(x, L);
+    const bool merged = ns > 1 || x.pt > 0;
+    if (merged) {
       MergeRec m;
       m.q_row = (cu_in_lds ? s_cuq[x.s] : a.cu_q[x.s]) + x.row0;
       m.ntok = x.ntok;
       m.nsplit = ns;
-      m.part = part_off;
+      m.part = own_off;
+      m.g_nsplit = ng;
+      m.g_part = x.pt > 0 ? s_gbase[s_glead[x.s]] + (x.s - s_glead[x.s]) : 0;
+      m.g_stride = x.pt > 0 ? s_gsize[s_glead[x.s]] : 0;
+      m.pad = 0;
       a.merges[merge_off++] = m;
     }
     for (int c = 0; c < ns; ++c) {
       ItemRec it;
       it.seq = x.s;
       it.row0 = x.row0;
-      it.t0 = c * L;
-      it.t1 = (c + 1 < ns ? (c + 1) * L : x.T);
-      it.part = ns > 1 ? part_off + c * x.ntok : -1;
-      it.pad[0] = it.pad[1] = it.pad[2] = 0;
-      const int pos = atomicAdd(&hist[kBuckets - 1 - ((it.t1 - it.t0) >> shift)], 1);
-      a.items[pos] = it;
+      it.t0 = x.pt + c * L;
+      it.t1 = (c + 1 < ns ? x.pt + (c + 1) * L : x.T);
+      it.part = merged ? own_off + c * x.ntok : -1;
+      it.gsize = 0;
+      it.pad[0] = it.pad[1] = 0;
+      a.items[atomicAdd(&hist[bucket(it.t1 - it.t0)], 1)] = it;
     }
-    if (ns > 1) part_off += ns * x.ntok;
+    for (int c = 0; x.gm && c < ng; ++c) {
+      ItemRec it;
+      it.seq = x.s;
+      it.row0 = 0;
+      it.t0 = c * L;
+      it.t1 = L > 0 ? min((c + 1) * L, x.pt) : x.pt;
+      it.part = s_gbase[x.s] + c * x.gm;
+      it.gsize = x.gm;
+      it.pad[0] = it.pad[1] = 0;
+      a.items[atomicAdd(&hist[bucket(it.t1 - it.t0)], 1)] = it;
+    }
+    if (merged) own_off += ns * x.ntok;
   }
   if (t == 0) {
     a.hdr->err = MC_OK;
@@ -390,6 +524,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     a.hdr->tile_tokens = a.tile_tokens;
     a.hdr->batch = a.batch;
     a.hdr->total_q = a.total_q;
+    a.hdr->num_groups_rows = tot_grp;
     a.hdr->magic = kPlanMagic;
   }
 }
@@ -517,9 +652,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const int seq = item[0], row0 = item[1];
   const int t0 = item[2];                            // first KV tile of the item (even)
   const int part = item[4];                          // >= 0: partial result, merged afterwards
+  const int gsize = item[5];                         // > 0: shared-prefix item over gsize sequences
   const int q0 = a.cu_q[seq], q_len = a.cu_q[seq + 1] - q0, b = a.begin[seq];
-  const int ntok = min(TOK, q_len - row0);          // valid tokens in this tile (>= 1)
-  const int first_pos = b + row0;                    // position of the tile's first token
+  // valid tokens in this tile (>= 1), and the position of the first one.  The rows of a
+  // shared-prefix item are the new tokens of gsize consecutive sequences; all of them lie
+  // beyond the prefix, so any position at or past the item's last key serves.
+  const int ntok = gsize > 0 ? gsize : min(TOK, q_len - row0);
+  const int first_pos = gsize > 0 ? item[3] * kBN : b + row0;
   // keys [64 t0, kv_len) are this item's: up to the end of its chunk, or of the tile's range
   const int kv_len = min(first_pos + ntok, item[3] * kBN);
   const int n_kv_tiles = (kv_len + kBN - 1) / kBN;   // (absolute) index after the last KV tile
@@ -869,14 +1008,19 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     const int rest = (int)(wk % per_tile);
     const int tt = rest / head_groups, h = rest % head_groups * 4 + wave;
     if (tt >= m.ntok || h >= a.hq) continue;
+    // partial row of chunk c: the shared prefix's chunks first, then the tile's own
+    auto row_of = [&](int c) {
+      return (int64_t)(c < m.g_nsplit ? m.g_part + c * m.g_stride
+                                      : m.part + (c - m.g_nsplit) * m.ntok + tt) * a.hq + h;
+    };
+    const int nchunks = m.g_nsplit + m.nsplit;
     float mx = -INFINITY;
-    for (int c = 0; c < m.nsplit; ++c)
-      mx = fmaxf(mx, a.part_lse[(int64_t)(m.part + c * m.ntok + tt) * a.hq + h]);
+    for (int c = 0; c < nchunks; ++c) mx = fmaxf(mx, a.part_lse[row_of(c)]);
     float den = 0.f;
     f32x2 acc = {0.f, 0.f};
 #pragma unroll 4
-    for (int c = 0; c < m.nsplit; ++c) {
-      const int64_t prow = (int64_t)(m.part + c * m.ntok + tt) * a.hq + h;
+    for (int c = 0; c < nchunks; ++c) {
+      const int64_t prow = row_of(c);
       const float w = __expf(a.part_lse[prow] - mx);   // exp(-inf) = 0 for a chunk with no key
       const f32x2 v = *reinterpret_cast<const f32x2*>(a.part_o + prow * mc::kHeadDim + 2 * lane);
       den += w;
@@ -922,11 +1066,21 @@ bool may_cut(const WorkspaceLayout& w, int hkv, int slots) {
   return w.part_cap > 0 && (int64_t)(w.max_tiles - w.batch) * hkv < (int64_t)kRoundsWanted * slots;
 }
 
+// Shared-prefix groups are made of sequences with one new token each: worth looking for only
+// when the batch could hold a fair share of those (fewer than two q tiles' worth of new tokens
+// per sequence on average), and possible only with room for partial rows.
+bool may_group(const WorkspaceLayout& w, int32_t total_q, int tile_tokens) {
+  return w.part_cap > 0 && w.batch >= 2 && w.batch <= kCuTilesInLds &&
+         (int64_t)total_q < 2ll * w.batch * tile_tokens;
+}
+
 // Upper bound of the planner's item count: a q tile with T KV tiles becomes at most T / L + 1
 // items, and the planner's chunk length L is at least (sum of T) x hkv / (kRoundsWanted x slots).
-int32_t item_bound(const WorkspaceLayout& w, int hkv, int slots) {
-  if (!may_cut(w, hkv, slots)) return w.max_tiles;
-  const int64_t b = (int64_t)w.max_tiles + (int64_t)kRoundsWanted * slots / hkv + 1;
+// A shared-prefix group adds at most one item per sequence beyond that.
+int32_t item_bound(const WorkspaceLayout& w, int hkv, int slots, bool groups) {
+  int64_t b = w.max_tiles;
+  if (may_cut(w, hkv, slots)) b += (int64_t)kRoundsWanted * slots / hkv + 1;
+  if (groups) b += w.batch;
   return (int32_t)(b < w.max_items ? b : w.max_items);
 }
 
@@ -988,7 +1142,8 @@ mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t ba
   a.hkv = pool->num_kv_heads;
   a.slots = device_slots();
   if (a.slots <= 0) return MC_ERR_HIP;
-  a.max_items = item_bound(w, a.hkv, a.slots);
+  a.allow_groups = may_group(w, total_q, kBM / G);
+  a.max_items = item_bound(w, a.hkv, a.slots, a.allow_groups);
   a.part_cap = w.part_cap;
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0,
                      static_cast<hipStream_t>(stream), a);
@@ -1028,7 +1183,9 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
   if (workspace_bytes < w.total) return MC_ERR_INVALID;
   const int slots = device_slots();
   if (slots <= 0) return MC_ERR_HIP;
-  const int64_t blocks = (int64_t)item_bound(w, pool->num_kv_heads, slots) * pool->num_kv_heads;
+  const bool groups = may_group(w, total_q, kBM / G);
+  const int64_t blocks =
+      (int64_t)item_bound(w, pool->num_kv_heads, slots, groups) * pool->num_kv_heads;
   if (blocks > 0x7fffffffll) return MC_ERR_UNSUPPORTED;
   char* ws = static_cast<char*>(workspace);
   AttnArgs a;
@@ -1058,7 +1215,7 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
   const bool gate = 4ll * batch >= w.max_tiles - batch;
   st = pool->dtype == MC_F16 ? launch_attn<_Float16>(G, gate, grid, hs, a)
                              : launch_attn<__bf16>(G, gate, grid, hs, a);
-  if (st != MC_OK || !may_cut(w, pool->num_kv_heads, slots)) return st;
+  if (st != MC_OK || !(may_cut(w, pool->num_kv_heads, slots) || groups)) return st;
   // the planner may have cut KV ranges: weigh the chunks together (does nothing if it did not)
   MergeArgs m;
   m.hdr = a.hdr;

@@ -372,3 +372,55 @@ def test_short_range_over_long_context_is_cut():
     h = plan_header(w)
     assert h["num_merges"] > 0, h
     check_attention(w, sample=256, seed=9)
+
+
+# ------------------------------------------------------------- shared prefixes ----
+def forked_decode_workload(seed, Hq, Hkv, dtype, groups, extra=()):
+    """groups: lists of (total tokens, tokens shared with the group's first sequence); every
+    sequence is a decode step (one new token).  extra: (n, b) of other sequences placed between
+    the groups (they break the neighbourhood)."""
+    lens, begins, forks = [], [], []
+    for gi, g in enumerate(groups):
+        first = len(lens)
+        for n, shared in g:
+            if len(lens) > first:
+                forks.append((len(lens), first, shared))
+            lens.append(n)
+            begins.append(n - 1)
+        if gi < len(extra):
+            lens.append(extra[gi][0])
+            begins.append(extra[gi][1])
+    w = small_workload(seed, dtype, Hq, Hkv, lens, begins)
+    for s, src, shared in forks:
+        w.share_prefix(s, src, shared)
+    return w
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype", [(32, 8, mi.BF16), (8, 8, mi.F16)])
+def test_decode_rows_sharing_a_prefix(Hq, Hkv, dtype):
+    # forks of a common prompt (Sec. 3.4 fork_sequence): their page tables start with the same
+    # pages.  Neighbouring decode rows attend the shared prefix together and their own
+    # remainders alone; results must equal plain per-sequence attention.
+    groups = [
+        [(1100, 0), (1500, 1024), (3000, 1024), (1040, 1024), (2000, 1024)],   # 64 shared pages
+        [(900, 0), (700, 592), (1300, 592)],                                   # 37 shared pages
+        [(800, 0), (900, 160)],                                                # too few: no group
+    ]
+    w = forked_decode_workload(400 + Hq, Hq, Hkv, dtype, groups, extra=[(700, 300), (90, 90)])
+    pool = DevPool(w)
+    db = DevBatch(w)
+    ws_bytes = mc.mc_attn_workspace_size(db.batch, db.total_q, w.num_q_heads, w.num_kv_heads)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    mc.mc_attn_plan(pool.desc, w.num_q_heads, db.batch, db.total_q, db.cu_q, db.begin,
+                    db.page_table, db.cu_pages, ws, ws_bytes)
+    mc.mc_attn_plan_check(ws)
+    h = ws[:64].view(torch.int32).cpu().numpy()
+    assert int(h[8]) > 0, h[:9]          # shared-prefix items were planned
+    check_attention(w)
+
+
+def test_more_forks_than_a_tile_holds():
+    # 40 forks of one 2048-token prompt with G = 4 (32 tokens a tile): two groups
+    groups = [[(2100 + 7 * i, 0 if i == 0 else 2048) for i in range(40)]]
+    w = forked_decode_workload(450, 32, 8, mi.BF16, groups)
+    check_attention(w)
