@@ -312,7 +312,8 @@ def main():
     other = {}
     if not args.no_copy_sweep:
         for name in ("paper-500-over-500", "paper-500-over-2500", "paper-500-over-4500",
-                     "decode-64", "decode-256", "decode-64-plus-prefill"):
+                     "decode-64", "decode-256", "decode-64-plus-prefill", "decode-64-no-forks",
+                     "decode-64-forks"):
             r = attention_only(name, 10)
             other[name] = {"ms": r["ms"], "TFLOPs": r["TFLOPs"],
                            "algorithmic_GBps": r["algorithmic_GBps"]}

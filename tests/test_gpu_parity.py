@@ -424,3 +424,13 @@ def test_more_forks_than_a_tile_holds():
     groups = [[(2100 + 7 * i, 0 if i == 0 else 2048) for i in range(40)]]
     w = forked_decode_workload(450, 32, 8, mi.BF16, groups)
     check_attention(w)
+
+
+def test_batch_larger_than_the_planner_keeps_in_lds():
+    # 1500 sequences (the planner keeps per-sequence offsets in LDS up to 1024): decode rows and
+    # short prefill ranges over short contexts
+    rng = mi.rng_for(460)
+    lens = [int(x) for x in rng.integers(1, 41, size=1500)]
+    begins = [n - 1 if i % 3 else int(rng.integers(0, n)) for i, n in enumerate(lens)]
+    w = small_workload(461, mi.BF16, 32, 8, lens, begins)
+    check_attention(w)
