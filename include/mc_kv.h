@@ -255,6 +255,34 @@ mc_status mc_addr_compress(const int32_t* pages /* host */, int32_t n,
 mc_status mc_addr_expand(const int32_t* runs /* host [2 n_runs] */, int32_t n_runs,
                          int32_t* pages_out /* host */, int32_t capacity, int32_t* n_out);
 
+/* ---- context cache index behind prep_recv ------------------------------------
+ * prep_recv "checks for the existence of prompt[:end] in the KV cache" and
+ * reports "the matched prefix length match_len" (Sec. 3.1, Sec. 3.2 Example 3).
+ * The index records which page holds the KV of which 16-token block of which
+ * token prefix: a trie over whole pages (a block is shared only if every token
+ * before it is the same, and a partly filled last page is never shared, since
+ * the sequence that owns it still appends to it).  Host only, not thread-safe.
+ * The index does not own pages: freeing, eviction and reference counts of
+ * shared pages are the caller's.
+ *   insert: the KV of tokens[0, n_tokens) lives in pages[0, n_tokens / 16)
+ *           (whole pages only; a block that is already recorded keeps its page).
+ *   match:  the longest recorded prefix of whole pages of tokens[0, n_tokens):
+ *           *match_len_out tokens (a multiple of 16), their pages in
+ *           pages_out[0, match_len / 16) (room for n_tokens / 16 entries).
+ *   mc_prep_recv(prompt, end): match prompt[0, end), then take pages for the rest
+ *           from the allocator: pages_out[0, ceil(end / 16)) = the matched pages
+ *           followed by fresh ones; MC_ERR_NO_PAGES changes nothing.
+ * Null handles or pointers (with n > 0) are MC_ERR_INVALID, negative counts
+ * MC_ERR_RANGE, a negative page id in insert MC_ERR_RANGE. */
+mc_status mc_prefix_index_create(void** index_out /* host */);
+mc_status mc_prefix_index_destroy(void* index);
+mc_status mc_prefix_index_insert(void* index, const int32_t* tokens /* host */, int32_t n_tokens,
+                                 const int32_t* pages /* host */);
+mc_status mc_prefix_index_match(void* index, const int32_t* tokens /* host */, int32_t n_tokens,
+                                int32_t* pages_out /* host */, int32_t* match_len_out);
+mc_status mc_prep_recv(void* index, void* alloc, const int32_t* prompt /* host */, int32_t end,
+                       int32_t* pages_out /* host */, int32_t* match_len_out);
+
 /* ---- calibration: MFMA issue rate ------------------------------------------
  * Not a step of the paper's path: a measurement aid for the attention roofline
  * (the attention of Sec. 3.4 is a dense contraction on v_mfma_f32_32x32x16 with

@@ -249,3 +249,40 @@ def addr_runs(pages) -> list:
         else:
             runs.append((int(p), 1))
     return runs
+
+
+# ---- context cache index behind prep_recv (paper Sec. 3.1, Sec. 3.2) ----
+class PrefixIndex:
+    """Which page holds the KV of which 16-token block of which token prefix, by brute force:
+    a dictionary from the whole token prefix up to and including a block to that block's page.
+    A block recorded earlier keeps its page."""
+
+    def __init__(self, page_size: int = 16):
+        self.page_size = page_size
+        self.page_of_prefix = {}
+
+    def insert(self, tokens, pages):
+        P = self.page_size
+        for k in range(len(tokens) // P):
+            self.page_of_prefix.setdefault(tuple(tokens[: (k + 1) * P]), int(pages[k]))
+
+    def match(self, tokens):
+        """(match_len, pages): the longest run of whole pages from the start that are recorded."""
+        P, pages = self.page_size, []
+        for k in range(len(tokens) // P):
+            key = tuple(tokens[: (k + 1) * P])
+            if key not in self.page_of_prefix:
+                break
+            pages.append(self.page_of_prefix[key])
+        return len(pages) * P, pages
+
+
+def prep_recv(index: PrefixIndex, alloc: Allocator, prompt, end: int):
+    """prep_recv(prompt, end): matched pages of prompt[0, end) followed by freshly allocated
+    ones for the rest; (pages, match_len), or None when the allocator cannot supply them."""
+    match_len, pages = index.match(list(prompt[:end]))
+    need = -(-end // index.page_size) - len(pages)
+    fresh = alloc.take(need)
+    if fresh is None:
+        return None
+    return pages + fresh, match_len

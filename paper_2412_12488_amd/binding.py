@@ -21,6 +21,8 @@ EXPORTS = [
     "mc_kv_pack_batch", "mc_kv_unpack_batch",
     "mc_mfma_probe_operand_bytes", "mc_mfma_probe",
     "mc_plan_remote_send", "mc_addr_compress", "mc_addr_expand",
+    "mc_prefix_index_create", "mc_prefix_index_destroy", "mc_prefix_index_insert",
+    "mc_prefix_index_match", "mc_prep_recv",
 ]
 
 
@@ -81,6 +83,11 @@ def lib():
     L.mc_plan_remote_send.argtypes = [i32, i32, i32, i32, C.POINTER(mc_send_plan)]
     L.mc_addr_compress.argtypes = [C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32)]
     L.mc_addr_expand.argtypes = [C.POINTER(i32), i32, C.POINTER(i32), i32, C.POINTER(i32)]
+    L.mc_prefix_index_create.argtypes = [C.POINTER(vp)]
+    L.mc_prefix_index_destroy.argtypes = [vp]
+    L.mc_prefix_index_insert.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(i32)]
+    L.mc_prefix_index_match.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32)]
+    L.mc_prep_recv.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32)]
     _lib = L
     return L
 
@@ -261,3 +268,34 @@ def mc_addr_expand(runs, capacity=None):
     _check(lib().mc_addr_expand(_i32_array(flat), len(runs), out, capacity, C.byref(n)),
            "mc_addr_expand")
     return [out[i] for i in range(n.value)]
+
+
+def mc_prefix_index_create():
+    h = C.c_void_p()
+    _check(lib().mc_prefix_index_create(C.byref(h)), "mc_prefix_index_create")
+    return h
+
+
+def mc_prefix_index_destroy(index):
+    _check(lib().mc_prefix_index_destroy(index), "mc_prefix_index_destroy")
+
+
+def mc_prefix_index_insert(index, tokens, pages):
+    _check(lib().mc_prefix_index_insert(index, _i32_array(tokens), len(tokens), _i32_array(pages)),
+           "mc_prefix_index_insert")
+
+
+def mc_prefix_index_match(index, tokens):
+    """Returns (match_len, pages of the matched whole pages)."""
+    out, m = (C.c_int32 * max(len(tokens) // 16, 1))(), C.c_int32(0)
+    _check(lib().mc_prefix_index_match(index, _i32_array(tokens), len(tokens), out, C.byref(m)),
+           "mc_prefix_index_match")
+    return m.value, [out[i] for i in range(m.value // 16)]
+
+
+def mc_prep_recv(index, alloc, prompt, end):
+    """Returns (page list for prompt[0, end): matched pages then fresh ones, match_len)."""
+    out, m = (C.c_int32 * max(-(-end // 16), 1))(), C.c_int32(0)
+    _check(lib().mc_prep_recv(index, alloc, _i32_array(prompt), end, out, C.byref(m)),
+           "mc_prep_recv")
+    return [out[i] for i in range(-(-end // 16))], m.value

@@ -2,7 +2,10 @@
 // prep_recv (paper Sec. 3.1: "allocates KV cache entries for the missing
 // subsequence"), and a host check of destination page tables.
 #include <algorithm>
+#include <array>
+#include <map>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "mc_common.h"
@@ -13,6 +16,31 @@ struct Allocator {
   int32_t num_pages;
   std::vector<int32_t> free_stack;  // back() is handed out next
   std::vector<uint8_t> state;       // 0 free, 1 handed out, 2 = seen earlier in this free call
+};
+
+// Trie over 16-token blocks: (parent node, the block's tokens) -> node; a node knows its page.
+struct PrefixIndex {
+  typedef std::pair<int32_t, std::array<int32_t, mc::kPage>> Key;
+  std::map<Key, int32_t> child;
+  std::vector<int32_t> page_of;   // by node id
+
+  static Key key(int32_t parent, const int32_t* block) {
+    Key k;
+    k.first = parent;
+    std::copy(block, block + mc::kPage, k.second.begin());
+    return k;
+  }
+  // whole pages of tokens[0, n) found: their pages go to pages_out (if given)
+  int32_t match(const int32_t* tokens, int32_t n, int32_t* pages_out) const {
+    int32_t node = -1, blocks = 0;
+    for (; (blocks + 1) * mc::kPage <= n; ++blocks) {
+      auto it = child.find(key(node, tokens + blocks * mc::kPage));
+      if (it == child.end()) break;
+      node = it->second;
+      if (pages_out) pages_out[blocks] = page_of[node];
+    }
+    return blocks;
+  }
 };
 
 }  // namespace
@@ -153,6 +181,68 @@ mc_status mc_addr_expand(const int32_t* runs, int32_t n_runs, int32_t* pages_out
     n += count;
   }
   *n_out = (int32_t)n;
+  return MC_OK;
+}
+
+mc_status mc_prefix_index_create(void** index_out) {
+  if (!index_out) return MC_ERR_INVALID;
+  PrefixIndex* x = new (std::nothrow) PrefixIndex();
+  if (!x) return MC_ERR_INVALID;
+  *index_out = x;
+  return MC_OK;
+}
+
+mc_status mc_prefix_index_destroy(void* index) {
+  if (!index) return MC_ERR_INVALID;
+  delete static_cast<PrefixIndex*>(index);
+  return MC_OK;
+}
+
+mc_status mc_prefix_index_insert(void* index, const int32_t* tokens, int32_t n_tokens,
+                                 const int32_t* pages) {
+  PrefixIndex* x = static_cast<PrefixIndex*>(index);
+  if (!x) return MC_ERR_INVALID;
+  if (n_tokens < 0) return MC_ERR_RANGE;
+  const int32_t blocks = n_tokens / mc::kPage;
+  if (blocks > 0 && (!tokens || !pages)) return MC_ERR_INVALID;
+  for (int32_t b = 0; b < blocks; ++b)
+    if (pages[b] < 0) return MC_ERR_RANGE;
+  int32_t node = -1;
+  for (int32_t b = 0; b < blocks; ++b) {
+    const PrefixIndex::Key k = PrefixIndex::key(node, tokens + b * mc::kPage);
+    auto it = x->child.find(k);
+    if (it == x->child.end()) {
+      x->page_of.push_back(pages[b]);
+      it = x->child.emplace(k, (int32_t)x->page_of.size() - 1).first;
+    }
+    node = it->second;
+  }
+  return MC_OK;
+}
+
+mc_status mc_prefix_index_match(void* index, const int32_t* tokens, int32_t n_tokens,
+                                int32_t* pages_out, int32_t* match_len_out) {
+  const PrefixIndex* x = static_cast<const PrefixIndex*>(index);
+  if (!x || !match_len_out) return MC_ERR_INVALID;
+  if (n_tokens < 0) return MC_ERR_RANGE;
+  if (n_tokens >= mc::kPage && (!tokens || !pages_out)) return MC_ERR_INVALID;
+  *match_len_out = x->match(tokens, n_tokens, pages_out) * mc::kPage;
+  return MC_OK;
+}
+
+mc_status mc_prep_recv(void* index, void* alloc, const int32_t* prompt, int32_t end,
+                       int32_t* pages_out, int32_t* match_len_out) {
+  const PrefixIndex* x = static_cast<const PrefixIndex*>(index);
+  if (!x || !alloc || !match_len_out) return MC_ERR_INVALID;
+  if (end < 0) return MC_ERR_RANGE;
+  if (end > 0 && (!prompt || !pages_out)) return MC_ERR_INVALID;
+  const int32_t total = (end + mc::kPage - 1) / mc::kPage;
+  std::vector<int32_t> matched(static_cast<size_t>(end / mc::kPage));
+  const int32_t m = x->match(prompt, end, matched.data());
+  mc_status st = mc_kv_alloc_pages(alloc, total - m, pages_out + m);   // all or nothing
+  if (st != MC_OK) return st;
+  std::copy(matched.begin(), matched.begin() + m, pages_out);
+  *match_len_out = m * mc::kPage;
   return MC_OK;
 }
 

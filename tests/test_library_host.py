@@ -229,3 +229,53 @@ def test_addr_compress_expand():
     with pytest.raises(mc.McError) as e:
         mc.mc_addr_expand([(0, 5)], capacity=4)
     assert e.value.status == mc.MC_ERR_RANGE
+
+
+def test_prefix_index_and_prep_recv_match_oracle():
+    rng = np.random.default_rng(11)
+    ix, oix = mc.mc_prefix_index_create(), oracle.PrefixIndex()
+    al, oal = mc.mc_kv_allocator_create(4096), oracle.Allocator(4096)
+    stems = [list(rng.integers(0, 50, size=int(rng.integers(0, 200)))) for _ in range(6)]
+    try:
+        for step in range(300):
+            stem = stems[int(rng.integers(0, len(stems)))]
+            cut = int(rng.integers(0, len(stem) + 1))
+            prompt = [int(x) for x in stem[:cut]] + [int(x) for x in rng.integers(0, 50, size=int(rng.integers(0, 80)))]
+            assert mc.mc_prefix_index_match(ix, prompt) == oix.match(prompt)
+            end = int(rng.integers(0, len(prompt) + 1))
+            want = oracle.prep_recv(oix, oal, prompt, end)
+            if want is None:
+                with pytest.raises(mc.McError) as e:
+                    mc.mc_prep_recv(ix, al, prompt, end)
+                assert e.value.status == mc.MC_ERR_NO_PAGES
+                continue
+            pages, m = mc.mc_prep_recv(ix, al, prompt, end)
+            assert (pages, m) == want
+            assert m % 16 == 0 and m <= end
+            if step % 2 == 0:                  # the sequence's whole pages become matchable
+                mc.mc_prefix_index_insert(ix, prompt[:end], pages)
+                oix.insert(prompt[:end], pages)
+            else:                              # or it goes away: only its fresh pages are returned
+                fresh = pages[m // 16:]
+                mc.mc_kv_free_pages(al, fresh)
+                oal.give(fresh)
+        assert mc.mc_kv_allocator_num_free(al) == oal.num_free
+    finally:
+        mc.mc_prefix_index_destroy(ix)
+        mc.mc_kv_allocator_destroy(al)
+
+
+def test_prefix_index_errors():
+    ix = mc.mc_prefix_index_create()
+    L = mc.lib()
+    assert L.mc_prefix_index_insert(None, None, 0, None) == mc.MC_ERR_INVALID
+    assert L.mc_prefix_index_insert(ix, None, -1, None) == mc.MC_ERR_RANGE
+    assert L.mc_prefix_index_insert(ix, None, 16, None) == mc.MC_ERR_INVALID
+    assert L.mc_prefix_index_insert(ix, None, 15, None) == mc.MC_OK       # no whole page: nothing to do
+    with pytest.raises(mc.McError) as e:
+        mc.mc_prefix_index_insert(ix, list(range(16)), [-3])
+    assert e.value.status == mc.MC_ERR_RANGE
+    assert L.mc_prefix_index_match(ix, None, 0, None, None) == mc.MC_ERR_INVALID
+    assert L.mc_prep_recv(ix, None, None, 0, None, None) == mc.MC_ERR_INVALID
+    assert mc.mc_prefix_index_match(ix, []) == (0, [])
+    mc.mc_prefix_index_destroy(ix)

@@ -477,3 +477,34 @@ def test_addr_runs():
     assert oracle.addr_runs([]) == []
     assert oracle.addr_runs([5, 6, 7, 9, 10, 3, 4, 4]) == [(5, 3), (9, 2), (3, 2), (4, 1)]
     assert oracle.addr_runs([2, 1, 0]) == [(2, 1), (1, 1), (0, 1)]
+
+
+# ---- context cache index behind prep_recv (Sec. 3.1) ----
+def test_prefix_index_hand_cases():
+    ix = oracle.PrefixIndex()
+    a = list(range(100, 150))                  # 50 tokens: 3 whole pages
+    ix.insert(a, [7, 8, 9])
+    assert ix.match(a) == (48, [7, 8, 9])
+    assert ix.match(a[:47]) == (32, [7, 8])    # the third page is not whole in the query
+    b = a[:32] + [999] + a[33:]                # differs in the third page
+    assert ix.match(b) == (32, [7, 8])
+    c = [5] + a[1:]                            # differs in the first token: nothing in common
+    assert ix.match(c) == (0, [])
+    # same block tokens under another prefix are another block
+    d = [1] * 16 + a[16:32]
+    ix.insert(d, [20, 21])
+    assert ix.match(d) == (32, [20, 21]) and ix.match(a[:32]) == (32, [7, 8])
+    # a block recorded earlier keeps its page
+    ix.insert(a, [70, 80, 90])
+    assert ix.match(a) == (48, [7, 8, 9])
+
+
+def test_prep_recv_oracle_allocates_only_the_unmatched_part():
+    ix, al = oracle.PrefixIndex(), oracle.Allocator(16)
+    prompt = list(range(200))
+    pages, m = oracle.prep_recv(ix, al, prompt, 100)      # nothing cached: 7 fresh pages
+    assert m == 0 and pages == [0, 1, 2, 3, 4, 5, 6] and al.num_free == 9
+    ix.insert(prompt[:100], pages)                         # 6 whole pages recorded
+    pages2, m2 = oracle.prep_recv(ix, al, prompt, 200)    # 96 tokens matched, 13 - 6 fresh
+    assert m2 == 96 and pages2[:6] == pages[:6] and pages2[6:] == [7, 8, 9, 10, 11, 12, 13]
+    assert oracle.prep_recv(ix, al, [9] * 64, 64) is None and al.num_free == 2   # all or nothing
