@@ -129,6 +129,61 @@ def attention_only(name, iters, values="normal"):
     return res
 
 
+def decode_step_latency(name, iters=50):
+    """One decode step = append + plan + attention (+ merge) of a decode batch, launched call by
+    call and replayed from a HIP graph (the calls allocate nothing and never synchronise, so the
+    step can be captured): microseconds per step, both ways."""
+    import numpy as np
+    import torch
+
+    import paper_2412_12488_amd as mc
+    dev = "cuda:0"
+    w = attention_workload(name)
+    Hq, Hkv = w.num_q_heads, w.num_kv_heads
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    pool = torch.randn(w.num_pages * 2 * Hkv * 16 * 128, dtype=torch.bfloat16, device=dev)
+    desc = mc.pool_desc(pool, 1, w.num_pages, Hkv, w.dtype)
+    tq = int(w.cu_q[-1])
+    q = torch.randn(tq * Hq * 128, dtype=torch.bfloat16, device=dev)
+    k = torch.randn(tq * Hkv * 128, dtype=torch.bfloat16, device=dev)
+    v = torch.randn(tq * Hkv * 128, dtype=torch.bfloat16, device=dev)
+    cu_q, begin = up(w.cu_q), up(w.b.astype(np.int32))
+    table, cu_pages = up(w.flat_page_table), up(w.cu_pages)
+    wsb = mc.mc_attn_workspace_size(w.batch, tq, Hq, Hkv)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    out = torch.empty((tq, Hq, 128), dtype=torch.int16, device=dev)
+    lse = torch.empty((tq, Hq), dtype=torch.float32, device=dev)
+
+    def step():
+        mc.mc_kv_append(desc, 0, k, v, w.batch, tq, cu_q, begin, table, cu_pages)
+        mc.mc_attn_plan(desc, Hq, w.batch, tq, cu_q, begin, table, cu_pages, ws, wsb)
+        mc.mc_prefix_prefill_attn(desc, 0, q, Hq, w.batch, tq, cu_q, begin, table, cu_pages, 0.0,
+                                  out, lse, ws, wsb)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3
+
+    eager = timed(step)
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    replay = timed(graph.replay)
+    del pool, q, k, v, out, lse, ws, graph
+    torch.cuda.empty_cache()
+    return {"eager_us": round(eager, 1), "graph_us": round(replay, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -317,6 +372,8 @@ def main():
             r = attention_only(name, 10)
             other[name] = {"ms": r["ms"], "TFLOPs": r["TFLOPs"],
                            "algorithmic_GBps": r["algorithmic_GBps"]}
+        # a whole decode step (append + plan + attention + merge), call by call and as a graph
+        other["decode_step_us"] = {n: decode_step_latency(n) for n in ("decode-8", "decode-64")}
 
     # ---- copies, each alone: this workload, then the long-context transfer size ----
     copy = {}

@@ -434,3 +434,59 @@ def test_batch_larger_than_the_planner_keeps_in_lds():
     begins = [n - 1 if i % 3 else int(rng.integers(0, n)) for i, n in enumerate(lens)]
     w = small_workload(461, mi.BF16, 32, 8, lens, begins)
     check_attention(w)
+
+
+# ------------------------------------------------------------------ HIP graph ----
+def test_decode_step_under_graph_capture():
+    """append + plan + attention (+ merge) of a decode step captured in a HIP graph: the calls
+    allocate nothing and never synchronise, so they can be captured; every replay, with fresh
+    Q/K/V in the same buffers, must give what the eager calls give."""
+    lens = [1500, 700, 2300, 64, 65, 3000, 999, 1200]
+    w = small_workload(470, mi.BF16, 32, 8, lens, [n - 1 for n in lens])
+    pool = DevPool(w)
+    opool = oracle.new_pool(pool.shape)
+    fill_both(w, pool, opool, upto_end=False)          # the cached prefixes
+    db = DevBatch(w)
+    Hq, Hkv = w.num_q_heads, w.num_kv_heads
+    ws_bytes = mc.mc_attn_workspace_size(db.batch, db.total_q, Hq, Hkv)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    q = torch.zeros((db.total_q, Hq, 128), dtype=torch.int16, device=DEV)
+    k = torch.zeros((db.total_q, Hkv, 128), dtype=torch.int16, device=DEV)
+    v = torch.zeros((db.total_q, Hkv, 128), dtype=torch.int16, device=DEV)
+    out = torch.zeros((db.total_q, Hq, 128), dtype=torch.int16, device=DEV)
+    lse = torch.zeros((db.total_q, Hq), dtype=torch.float32, device=DEV)
+
+    def step():
+        mc.mc_kv_append(pool.desc, 0, k, v, db.batch, db.total_q, db.cu_q, db.begin,
+                        db.page_table, db.cu_pages)
+        mc.mc_attn_plan(pool.desc, Hq, db.batch, db.total_q, db.cu_q, db.begin, db.page_table,
+                        db.cu_pages, ws, ws_bytes)
+        mc.mc_prefix_prefill_attn(pool.desc, 0, q, Hq, db.batch, db.total_q, db.cu_q, db.begin,
+                                  db.page_table, db.cu_pages, 0.0, out, lse, ws, ws_bytes)
+
+    def fresh(seed):
+        g = torch.Generator(device=DEV).manual_seed(seed)
+        for t in (q, k, v):
+            t.copy_(torch.randn(t.shape, generator=g, device=DEV).to(torch.bfloat16).view(torch.int16))
+
+    fresh(1)
+    step()                                   # eager once (also warms the library up)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for seed in (2, 3, 4):
+        fresh(seed)
+        graph.replay()
+        torch.cuda.synchronize()
+        got_o, got_l = out.clone(), lse.clone()
+        out.zero_()
+        lse.zero_()
+        step()                               # the program's own eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(got_o, out) and torch.equal(got_l, lse), seed
+    assert torch.isfinite(lse).all()
