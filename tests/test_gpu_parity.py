@@ -490,3 +490,81 @@ def test_decode_step_under_graph_capture():
         torch.cuda.synchronize()
         assert torch.equal(got_o, out) and torch.equal(got_l, lse), seed
     assert torch.isfinite(lse).all()
+
+
+# ------------------------------------------------- the calls together: one prompt, two engines ----
+@pytest.mark.parametrize("sender_cached,receiver_cached", [(192, 64), (64, 192), (0, 0), (384, 0),
+                                                           (128, 128)])
+def test_remote_send_flow_for_the_prefix_matching_cases(sender_cached, receiver_cached):
+    """prep_recv on the receiver, remote_send on the sender (copy what is cached, prefill the
+    rest, send what the receiver lacks), start_generate on the receiver (Sec. 3.1, Sec. 3.2,
+    Sec. 3.4 cases 1 and 2): afterwards the receiver holds exactly the prompt's KV and its
+    last-token attention equals the oracle's."""
+    Hq, Hkv, n, pages_total = 32, 8, 400, 64
+    end = n - 1                                             # the receiver prefills the last token
+    w = small_workload(500 + sender_cached + receiver_cached, mi.BF16, Hq, Hkv, [n], [0],
+                       num_pages=pages_total)
+    prompt = [int(x) for x in mi.rng_for(w.seed, 42).integers(0, 32000, size=n)]
+    k_all, v_all = w.kv(0)
+
+    def engine(cached):
+        """An engine that already served prompt[:cached]: pool, allocator, index, that KV."""
+        pool = DevPool(w)
+        pool.t.fill_(0x7fc1)
+        al, ix = mc.mc_kv_allocator_create(pages_total), mc.mc_prefix_index_create()
+        mc.mc_kv_alloc_pages(al, 3)                         # the engines' page ids differ
+        if cached:
+            pages, m = mc.mc_prep_recv(ix, al, prompt, cached)
+            assert m == 0
+            wc = mi.Workload("c", w.seed, w.dtype, 1, Hq, Hkv, pages_total, np.array([cached]),
+                             np.array([0]), [np.array(pages, dtype=np.int32)])
+            gpu_append(pool, 0, dev(k_all[:cached]), dev(v_all[:cached]), DevBatch(wc))
+            mc.mc_prefix_index_insert(ix, prompt[:cached], pages)
+        return pool, al, ix
+
+    pool_a, al_a, ix_a = engine(sender_cached)
+    pool_b, al_b, ix_b = engine(receiver_cached)
+    # receiver: prep_recv(prompt, end) -> where to send, and how much it already has
+    pages_b, match_b = mc.mc_prep_recv(ix_b, al_b, prompt, end)
+    assert match_b == receiver_cached
+    # sender: remote_send(prompt, kv_addr_info, begin = 0, end)
+    pages_a, match_a = mc.mc_prep_recv(ix_a, al_a, prompt, end)
+    assert match_a == sender_cached
+    plan = mc.mc_plan_remote_send(match_a, match_b, 0, end)
+    tab_a, tab_b = np.array(pages_a, dtype=np.int32), np.array(pages_b, dtype=np.int32)
+    # the compressed address list travels and comes back unchanged
+    assert mc.mc_addr_expand(mc.mc_addr_compress(pages_b)) == pages_b
+    p0, p1 = plan["prefill"]
+    if p1 > p0:                                             # KV of what the sender lacks
+        wp = mi.Workload("p", w.seed, w.dtype, 1, Hq, Hkv, pages_total, np.array([p1]),
+                         np.array([p0]), [tab_a])
+        gpu_append(pool_a, 0, dev(k_all[p0:p1]), dev(v_all[p0:p1]), DevBatch(wp))
+        out_p, lse_p = gpu_attention(pool_a, 0, dev(w.q(0)[p0:p1]), DevBatch(wp))
+        assert torch.isfinite(lse_p).all()
+    for s0, s1 in (plan["copy"], plan["send"]):             # pack -> wire -> unpack
+        if s1 > s0:
+            buf = torch.zeros(2 * (s1 - s0) * Hkv * 128, dtype=torch.int16, device=DEV)
+            mc.mc_kv_pack_range(pool_a.desc, 0, 1, dev(tab_a), len(tab_a), s0, s1, buf)
+            mc.mc_kv_unpack_range(pool_b.desc, 0, 1, dev(tab_b), len(tab_b), s0, s1, buf)
+    # the receiver now holds prompt[0, end): packed out of its pool it is the prompt's KV, bit for bit
+    got = torch.zeros(2 * end * Hkv * 128, dtype=torch.int16, device=DEV)
+    mc.mc_kv_pack_range(pool_b.desc, 0, 1, dev(tab_b), len(tab_b), 0, end, got)
+    want = np.concatenate([k_all[:end].reshape(-1), v_all[:end].reshape(-1)])
+    assert np.array_equal(bits(got), want)
+    # receiver: start_generate(prompt, begin = end): the last token over everything before it
+    wl = mi.Workload("l", w.seed, w.dtype, 1, Hq, Hkv, pages_total, np.array([n]), np.array([end]),
+                     [tab_b])
+    gpu_append(pool_b, 0, dev(k_all[end:n]), dev(v_all[end:n]), DevBatch(wl))
+    out, lse = gpu_attention(pool_b, 0, dev(w.q(0)[end:n]), DevBatch(wl))
+    # oracle: the same sequence in a pool of its own
+    wo = mi.Workload("o", w.seed, w.dtype, 1, Hq, Hkv, pages_total, np.array([n]), np.array([end]),
+                     [w.page_tables[0]])
+    opool = oracle.new_pool(pool_b.shape)
+    oracle.append(opool, pool_b.shape, 0, k_all, v_all, 0, w.page_tables[0])
+    ro, rl = oracle_rows(wo, opool, pool_b.shape, 0, 0, w.q(0)[end:n])
+    assert np.max(np.abs(oracle.decode(bits(out), w.dtype) - ro)) <= O_TOL
+    assert np.max(np.abs(lse.cpu().numpy().astype(np.float64) - rl)) <= LSE_TOL
+    for h in (ix_a, ix_b):
+        mc.mc_prefix_index_destroy(h)
+    for h in (al_a, al_b):
+        mc.mc_kv_allocator_destroy(h)
