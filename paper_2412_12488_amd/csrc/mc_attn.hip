@@ -56,7 +56,8 @@ struct PlanHeader {
   int32_t num_merges; // q tiles whose KV range was cut into several chunks
   int32_t chunk_tiles;  // chunk length the planner settled on (KV tiles); 0 = nothing was cut
   int32_t num_groups_rows;  // partial rows written by shared-prefix items (0 = no groups)
-  int32_t pad[7];
+  int32_t tail_chunks;  // chunks per q tile of the remainder round (0 = not applied)
+  int32_t pad[6];
 };
 static_assert(sizeof(PlanHeader) == 64, "header is 64 bytes");
 
@@ -83,6 +84,7 @@ struct MergeRec {
 static_assert(sizeof(MergeRec) == 32, "merge record is 32 bytes");
 
 constexpr int kCuTilesInLds = 1024;
+constexpr int kTailTilesMax = 2048;   // q tiles up to which the remainder round is looked at
 constexpr int kMinSharedTiles = 8;    // a shared prefix shorter than 512 tokens is not worth a group
 constexpr int kMinChunkTiles = 8;     // never cut a KV range into pieces shorter than 512 keys
 constexpr int kRoundsWanted = 4;      // cut only while the launch has fewer items than 4 per slot
@@ -205,6 +207,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   __shared__ int s_common[kCuTilesInLds], s_gp[kCuTilesInLds], s_glead[kCuTilesInLds],
       s_gsize[kCuTilesInLds], s_gbase[kCuTilesInLds];
   __shared__ int s_groups;
+  // remainder round: flags of the q tiles that are cut, the cost bucket at the boundary and how
+  // many tiles of it are taken
+  __shared__ uint8_t s_tailflag[kTailTilesMax];
+  __shared__ int s_tail_bucket, s_tail_take, s_tail_taken;
   __shared__ unsigned long long s_cost;
   const int t = threadIdx.x;
   if (t == 0) { s_err = 0; s_maxcost = 1; s_cost = 0; s_chunk = 0; s_part_tokens = 0; }
@@ -431,23 +437,71 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   // without cuts the groups still need partial rows: no room, no groups
   if (L == 0 && groups && total_part_rows(0) > a.part_cap) groups = false;
 
-  // 5. items and merge records: count per contiguous range of tiles, scan, histogram of costs
-  const int tper = (total_tiles + kPlanThreads - 1) / kPlanThreads;
-  const int i_lo = min(t * tper, total_tiles), i_hi = min(i_lo + tper, total_tiles);
   int shift = 0;
   while ((s_maxcost >> shift) >= kBuckets) ++shift;
   auto bucket = [&](int len) { return kBuckets - 1 - (len >> shift); };
+
+  // 4b. remainder round.  Between one and kRoundsWanted rounds of uncut, similar items the last
+  //     round is the problem: n items on S slots take ceil(n / S) rounds although the last one
+  //     may hold few items.  The n mod S shortest items (they run last) are then cut into
+  //     c = ceil(S / (n mod S)) chunks each, which fill that round with items 1/c as long.
+  int tail_c = 0;
+  {
+    const int64_t n = (int64_t)total_tiles * a.hkv;
+    const int rem = (int)(n % a.slots);
+    const int rem_tiles = rem / a.hkv;
+    const int c = rem > 0 ? min(8, (a.slots + rem - 1) / rem) : 0;
+    if (L == 0 && !groups && total_tiles <= kTailTilesMax && n >= a.slots &&
+        n < (int64_t)kRoundsWanted * a.slots && rem_tiles >= 1 && 10 * rem <= 7 * a.slots && c >= 2 &&
+        (int64_t)rem_tiles * a.tile_tokens * c <= a.part_cap) {
+      if (t == 0) { s_tail_bucket = kBuckets; s_tail_take = 0; s_tail_taken = 0; }
+      for (int i = t; i < total_tiles; i += kPlanThreads) atomicAdd(&hist[bucket(locate(i).T)], 1);
+      __syncthreads();
+      // shortest first: walk the buckets from the last to the first until rem_tiles tiles are in
+      constexpr int kPer = kBuckets / kPlanThreads;
+      int local[kPer], sum = 0;
+      for (int i = 0; i < kPer; ++i) { local[i] = hist[kBuckets - 1 - (t * kPer + i)]; sum += local[i]; }
+      int tot, before = block_exclusive_scan(sum, scan, &tot);
+      for (int i = 0; i < kPer; ++i) {
+        if (before < rem_tiles && before + local[i] >= rem_tiles) {
+          s_tail_bucket = kBuckets - 1 - (t * kPer + i);
+          s_tail_take = rem_tiles - before;
+        }
+        before += local[i];
+      }
+      __syncthreads();
+      for (int i = t; i < total_tiles; i += kPlanThreads) {
+        const int bk = bucket(locate(i).T);
+        s_tailflag[i] = bk > s_tail_bucket ||
+                        (bk == s_tail_bucket && atomicAdd(&s_tail_taken, 1) < s_tail_take);
+      }
+      for (int i = t; i < kBuckets; i += kPlanThreads) hist[i] = 0;
+      __syncthreads();
+      tail_c = c;
+    }
+  }
+  // chunk length of q tile i: the batch's, or its own if it is cut for the remainder round
+  auto chunk_len = [&](int i, const Tile& x) {
+    if (tail_c == 0 || !s_tailflag[i]) return L;
+    const int len = ((x.T + tail_c - 1) / tail_c + 1) & ~1;
+    return max(len, kMinChunkTiles);
+  };
+
+  // 5. items and merge records: count per contiguous range of tiles, scan, histogram of costs
+  const int tper = (total_tiles + kPlanThreads - 1) / kPlanThreads;
+  const int i_lo = min(t * tper, total_tiles), i_hi = min(i_lo + tper, total_tiles);
   int n_items = 0, n_own = 0, n_grp = 0, n_merge = 0;
   for (int i = i_lo; i < i_hi; ++i) {
     const Tile x = locate(i);
-    const int ns = own_splits(x, L), ng = x.gm ? grp_splits(x, L) : 0;
+    const int Li = chunk_len(i, x);
+    const int ns = own_splits(x, Li), ng = x.gm ? grp_splits(x, Li) : 0;
     n_items += ns + ng;
     if (ns > 1 || x.pt > 0) { n_own += ns * x.ntok; ++n_merge; }
     n_grp += ng * x.gm;
     for (int c = 0; c < ns; ++c)
-      atomicAdd(&hist[bucket(c + 1 < ns ? L : x.T - x.pt - c * L)], 1);
+      atomicAdd(&hist[bucket(c + 1 < ns ? Li : x.T - x.pt - c * Li)], 1);
     for (int c = 0; c < ng; ++c)
-      atomicAdd(&hist[bucket(L > 0 ? min(L, x.pt - c * L) : x.pt)], 1);
+      atomicAdd(&hist[bucket(Li > 0 ? min(Li, x.pt - c * Li) : x.pt)], 1);
   }
   int tot_items, tot_own, tot_grp, tot_merge;
   block_exclusive_scan(n_items, scan, &tot_items);
@@ -471,14 +525,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     int off = tot_own + grp_off;
     for (int i = i_lo; i < i_hi; ++i) {
       const Tile x = locate(i);
-      if (x.gm) { s_gbase[x.s] = off; off += grp_splits(x, L) * x.gm; }
+      if (x.gm) { s_gbase[x.s] = off; off += grp_splits(x, chunk_len(i, x)) * x.gm; }
     }
     __syncthreads();
   }
   // 6. emit: counting sort of the items by cost (number of KV tiles), heaviest first
   for (int i = i_lo; i < i_hi; ++i) {
     const Tile x = locate(i);
-    const int ns = own_splits(x, L), ng = grp_splits(x, L);
+    const int Li = chunk_len(i, x);
+    const int ns = own_splits(x, Li), ng = grp_splits(x, Li);
     const bool merged = ns > 1 || x.pt > 0;
     if (merged) {
       MergeRec m;
@@ -496,8 +551,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       ItemRec it;
       it.seq = x.s;
       it.row0 = x.row0;
-      it.t0 = x.pt + c * L;
-      it.t1 = (c + 1 < ns ? x.pt + (c + 1) * L : x.T);
+      it.t0 = x.pt + c * Li;
+      it.t1 = (c + 1 < ns ? x.pt + (c + 1) * Li : x.T);
       it.part = merged ? own_off + c * x.ntok : -1;
       it.gsize = 0;
       it.pad[0] = it.pad[1] = 0;
@@ -507,8 +562,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       ItemRec it;
       it.seq = x.s;
       it.row0 = 0;
-      it.t0 = c * L;
-      it.t1 = L > 0 ? min((c + 1) * L, x.pt) : x.pt;
+      it.t0 = c * Li;
+      it.t1 = Li > 0 ? min((c + 1) * Li, x.pt) : x.pt;
       it.part = s_gbase[x.s] + c * x.gm;
       it.gsize = x.gm;
       it.pad[0] = it.pad[1] = 0;
@@ -525,6 +580,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     a.hdr->batch = a.batch;
     a.hdr->total_q = a.total_q;
     a.hdr->num_groups_rows = tot_grp;
+    a.hdr->tail_chunks = tail_c;
     a.hdr->magic = kPlanMagic;
   }
 }
