@@ -4,10 +4,18 @@
 // Sec. 3.4 attention(qkv_data)), and the planning step that precedes it
 // (Sec. 3.4 begin_forward: plan the metadata once for all layers).
 //
+// Work
+//   * plan_kernel cuts the ragged batch into work items: a q tile (128 rows = TOK
+//     tokens x G query heads of one kv head's group, TOK = 128/G, token-major) over
+//     a range of 64-key KV tiles - the whole range, or a chunk of it when the batch
+//     alone would not fill the GPU (decode steps, short ranges over long contexts),
+//     or the prefix that neighbouring decode rows share (fork_sequence, Sec. 3.4).
+//     Items are ordered longest first.
+//   * attn_kernel: one workgroup (4 wavefronts of 64) per (item, kv head), so every
+//     K/V byte staged in LDS serves the whole GQA group.  Items that cover a whole
+//     range write out/lse; the others write partial rows that merge_kernel weighs
+//     together by their log-sum-exp.
 // Kernel shape
-//   * one workgroup (4 wavefronts of 64) per (q tile, kv head).  A q tile is
-//     128 rows = TOK tokens x G query heads of one kv head's group (TOK = 128/G),
-//     so every K/V byte staged in LDS serves the whole GQA group.
 //   * the KV loop walks 64-key tiles (4 pages) through the page table; each page
 //     contributes one contiguous 4 KiB run of K and one of V for this kv head.
 //   * S^T = K Q^T on v_mfma_f32_32x32x16 (A = K rows from LDS, B = Q held in
@@ -21,8 +29,6 @@
 //     reads (V) spread over all banks.
 #include <math.h>
 
-#include <type_traits>
-
 #include "mc_common.h"
 
 namespace {
@@ -34,7 +40,6 @@ using mc::kRowBytes;
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -195,9 +200,9 @@ __device__ int block_inclusive_max_scan(int v, int* lds) {
 // and orders the items by decreasing number of KV tiles (longest first), so that the tail of
 // the launch is made of short items.
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
-  __shared__ int scan[kPlanThreads];
+  __shared__ int scan[kPlanThreads / 64];   // wavefront totals of the block scans
   __shared__ int hist[kBuckets];
-  __shared__ int s_err, s_maxcost, s_chunk, s_part_tokens;
+  __shared__ int s_err, s_maxcost, s_part_tokens;
   // per-sequence arrays of batches that fit: the searches and tile look-ups below stay in LDS
   __shared__ int s_cu[kCuTilesInLds + 1], s_cuq[kCuTilesInLds + 1], s_beg[kCuTilesInLds],
       s_cup[kCuTilesInLds + 1];
@@ -213,7 +218,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   __shared__ int s_tail_bucket, s_tail_take, s_tail_taken;
   __shared__ unsigned long long s_cost;
   const int t = threadIdx.x;
-  if (t == 0) { s_err = 0; s_maxcost = 1; s_cost = 0; s_chunk = 0; s_part_tokens = 0; }
+  if (t == 0) { s_err = 0; s_maxcost = 1; s_cost = 0; s_part_tokens = 0; }
   for (int i = t; i < kBuckets; i += kPlanThreads) hist[i] = 0;
   const bool cu_in_lds = a.batch <= kCuTilesInLds;
   if (cu_in_lds) {
@@ -634,7 +639,6 @@ struct AttnArgs {
 
 typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef __attribute__((address_space(1))) const void* gbl_void_ptr;
 // Read-only metadata is addressed through the constant address space so that wave-uniform
 // reads stay scalar loads (no vector-memory counter involved) even after LDS copies and stores.
 typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
