@@ -666,7 +666,10 @@ __device__ __forceinline__ int k_swz(int row, int chunk) { return row * kRowByte
 __device__ __forceinline__ int v_swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ ((row & 3) << 2)) << 4); }
 
 // max of three floats in one instruction (written as assembly: through fmaxf every score would
-// first pass a NaN-quieting instruction of its own)
+// first pass a NaN-quieting instruction of its own).  The compiler does not see what an assembly
+// statement reads, so it inserts none of the wait states a vector instruction needs before it
+// may read the registers an MFMA is still writing: the first read of a fresh MFMA result goes
+// through fmaxf, which the compiler does protect, and only the later ones through this.
 __device__ __forceinline__ float max3(float a, float b, float c) {
   float r;
   asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
@@ -819,10 +822,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     }
   };
   // the other 16 keys of the row's half tile sit in lane l ^ 32: swap the wave's halves on the VALU
+  // with one v_permlane32_swap: given the value in both operands, the first comes back holding
+  // the lower half's value in both halves and the second the upper half's.  Written as assembly
+  // (with the two wait states the instruction needs after a vector write of its operands):
+  // through __builtin_amdgcn_permlane32_swap this compiler hands out the first result twice.
   auto max_across_halves = [&](float mx) __attribute__((always_inline)) {
-    const uint32_t bits = __builtin_bit_cast(uint32_t, mx);
-    const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
-    return fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
+    uint32_t lo = __builtin_bit_cast(uint32_t, mx), hi = lo;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+    return fmaxf(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
   };
 
   f32x16 o_acc[4];
@@ -855,9 +862,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 #pragma unroll
     for (int f = 0; f < 8; ++f) s_a = Mfma<T>::run(k_frag(lds_k, f), qreg[f], f == 0 ? zero16 : s_a);
     if (n_full <= 2 * t0) mask_half(2 * t0, s_a);
-    float mx = s_a[0];
+    float mx = fmaxf(s_a[0], s_a[1]);
 #pragma unroll
-    for (int i = 0; i < 16; i += 2) mx = max3(mx, s_a[i], s_a[i + 1]);
+    for (int i = 2; i < 16; i += 2) mx = max3(mx, s_a[i], s_a[i + 1]);
     mx_cur = max_across_halves(mx);
   }
   __syncthreads();   // every wave has read K half 0 before tile 0 overwrites its slot
@@ -906,7 +913,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     if (mask_next) mask_half(h + 1, s_next);
     // ---- phase 2: 8 steps.  Step u: V fragment u (16-key step st = u >> 2 -> operand words
     //      4 st..4 st+3, d chunk dc = u & 3); row max over register pair u of S(h+1).
-    float mx = -INFINITY;
+    float mx;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int st = u >> 2, dc = u & 3;
@@ -914,7 +921,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
       o_acc[dc] = Mfma<T>::run(vf[u % kAhead], __builtin_bit_cast(vec8, pw), o_acc[dc]);
       if (u + kAhead < 8) vf[u % kAhead] = v_frag(v_cur, crow, u + kAhead);
       else if (fetch_after) kf[u % kAhead] = k_frag(k_after, u + kAhead - 8);
-      mx = max3(mx, s_next[2 * u], s_next[2 * u + 1]);
+      mx = u == 0 ? fmaxf(s_next[0], s_next[1]) : max3(mx, s_next[2 * u], s_next[2 * u + 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
     mx_cur = max_across_halves(mx);

@@ -177,7 +177,7 @@ def test_transfer_then_attend_equals_local_attention():
 
 
 # ---------------------------------------------------------------- attention ----
-def check_attention(w, layer=0, scale=None, sample=None, seed=0):
+def check_attention(w, layer=0, scale=None, sample=None, seed=0, o_tol=O_TOL):
     # every slot that is never appended holds NaN bit patterns: unwritten slots of a
     # sequence's last page and foreign pages must not leak into the result
     pool = DevPool(w)
@@ -207,7 +207,7 @@ def check_attention(w, layer=0, scale=None, sample=None, seed=0):
         assert np.all(np.isfinite(go)) and np.all(np.isfinite(gl))
         worst_o = max(worst_o, float(np.max(np.abs(go - ro))))
         worst_l = max(worst_l, float(np.max(np.abs(gl - rl))))
-    assert worst_o <= O_TOL, worst_o
+    assert worst_o <= o_tol, worst_o
     assert worst_l <= LSE_TOL, worst_l
     return worst_o, worst_l
 
@@ -568,3 +568,42 @@ def test_remote_send_flow_for_the_prefix_matching_cases(sender_cached, receiver_
         mc.mc_prefix_index_destroy(h)
     for h in (al_a, al_b):
         mc.mc_kv_allocator_destroy(h)
+
+
+# ------------------------------------------------------- value distributions ----
+def _scaled_kv(w, k_gain=None, v_gain=1.0, ramp=0.0, const_k=False):
+    """Replace the workload's K/V by a transformed copy: K x k_gain (wide score range), K plus
+    a ramp along the token axis in the direction of a fixed vector (scores that keep rising, so
+    the running max moves tile after tile), K constant (uniform softmax), V x v_gain."""
+    base = w.kv
+    dt = w.dtype
+
+    def kv(seq, layer=0):
+        k, v = base(seq, layer)
+        kf = oracle.decode(k, dt)
+        vf = oracle.decode(v, dt) * v_gain
+        if const_k:
+            kf = np.broadcast_to(kf[:1], kf.shape).copy()
+        if k_gain is not None:
+            kf = kf * k_gain
+        if ramp:
+            kf = kf + ramp * np.arange(kf.shape[0])[:, None, None] * np.sign(kf[:1])
+        return (mi.f32_to_bits(kf.astype(np.float32), dt), mi.f32_to_bits(vf.astype(np.float32), dt))
+    w.kv = kv
+    return w
+
+
+@pytest.mark.parametrize("kind", ["wide", "rising", "uniform", "big_v"])
+@pytest.mark.parametrize("dtype", [mi.BF16, mi.F16])
+def test_attention_value_distributions(kind, dtype):
+    lens, begins = [700, 333, 1], [130, 0, 0]
+    w = small_workload(600 + len(kind), dtype, 8, 2, lens, begins)
+    if kind == "wide":        # scaled scores ~ N(0, 6^2): exp2 range of dozens between keys
+        _scaled_kv(w, k_gain=6.0)
+    elif kind == "rising":    # every tile's max exceeds the last one's: the reference max keeps moving
+        _scaled_kv(w, ramp=0.02)
+    elif kind == "uniform":   # all keys equal: softmax is uniform, LSE = s + ln(i + 1)
+        _scaled_kv(w, const_k=True)
+    else:                     # V x 3: the output and its 2-byte rounding scale with V, so does the bar
+        _scaled_kv(w, v_gain=3.0)
+    check_attention(w, o_tol=3 * O_TOL if kind == "big_v" else O_TOL)
