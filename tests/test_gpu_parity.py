@@ -595,9 +595,10 @@ def _scaled_kv(w, k_gain=None, v_gain=1.0, ramp=0.0, const_k=False):
 
 @pytest.mark.parametrize("kind", ["wide", "rising", "uniform", "big_v"])
 @pytest.mark.parametrize("dtype", [mi.BF16, mi.F16])
-def test_attention_value_distributions(kind, dtype):
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (8, 8), (16, 2)])
+def test_attention_value_distributions(kind, dtype, Hq, Hkv):
     lens, begins = [700, 333, 1], [130, 0, 0]
-    w = small_workload(600 + len(kind), dtype, 8, 2, lens, begins)
+    w = small_workload(600 + len(kind) + Hq, dtype, Hq, Hkv, lens, begins)
     if kind == "wide":        # scaled scores ~ N(0, 6^2): exp2 range of dozens between keys
         _scaled_kv(w, k_gain=6.0)
     elif kind == "rising":    # every tile's max exceeds the last one's: the reference max keeps moving
@@ -607,3 +608,15 @@ def test_attention_value_distributions(kind, dtype):
     else:                     # V x 3: the output and its 2-byte rounding scale with V, so does the bar
         _scaled_kv(w, v_gain=3.0)
     check_attention(w, o_tol=3 * O_TOL if kind == "big_v" else O_TOL)
+
+
+@pytest.mark.parametrize("dtype", [mi.BF16, mi.F16])
+def test_wide_scores_through_chunks_and_merge(dtype):
+    # decode rows and a short range over long contexts (the planner cuts them into chunks) with
+    # scores spanning dozens of powers of two: chunk LSEs far apart, weights down to exactly 0
+    lens = [2500, 1800, 3000, 900]
+    begins = [2499, 1799, 2900, 899]
+    w = small_workload(640, dtype, 32, 8, lens, begins)
+    _scaled_kv(w, k_gain=6.0)
+    assert plan_header(w)["num_merges"] > 0
+    check_attention(w)
