@@ -3,20 +3,25 @@
  *
  * The calls are the data-plane half of the unified KV cache interface of
  * "A System for Microserving of LLMs" (arXiv 2412.12488), Sec. 3.4:
- *   - prep_recv allocates KV entries (page index + slot index, Sec. 3.2
- *     Example 2) for the part of a prompt the engine does not hold
- *                                                   -> mc_kv_alloc_pages
+ *   - prep_recv matches the prompt against the engine's context cache and
+ *     allocates KV entries (page index + slot index, Sec. 3.2 Examples 2, 3)
+ *     for the part the engine does not hold; the addresses travel in a
+ *     compressed form
+ *            -> mc_prefix_index_*, mc_prep_recv, mc_kv_alloc_pages, mc_addr_*
  *   - begin_forward plans the metadata once for all attention layers
  *                                                   -> mc_attn_plan
  *   - attention(qkv_data) writes the new K/V into the cache and attends the
  *     new tokens over the cached prefix and themselves (start_generate
  *     prefills prompt[begin:] over the cached prompt[:begin], Sec. 3.1; the
- *     balanced split continues with prompt[s:], Sec. 3.3)
+ *     balanced split continues with prompt[s:], fused with the decode steps
+ *     of other sequences, Sec. 3.3; sequences forked from one prompt share its
+ *     pages, Sec. 3.4)
  *                                   -> mc_kv_append, mc_prefix_prefill_attn
  *   - remote_send moves the KV of prompt[begin:end] into the entries the
  *     receiver reserved (Sec. 3.1, Sec. 3.5); on one GPU the wire is replaced
- *     by a contiguous buffer in HBM
- *                                   -> mc_kv_pack_range, mc_kv_unpack_range
+ *     by a contiguous buffer in HBM; which ranges the sender copies, computes
+ *     and sends follows from what the two engines have cached (Sec. 3.4)
+ *            -> mc_plan_remote_send, mc_kv_pack_range, mc_kv_unpack_range
  *
  * The paper fixes no dtype, page size, page layout, softmax scale or LSE base;
  * the choices below are this library's.
@@ -26,7 +31,7 @@
  *     current device, "host" = ordinary host memory.
  *   - All device memory is owned by the caller and must stay valid until the
  *     work queued on `stream` has finished.  The library owns only the host
- *     allocator object made by mc_kv_allocator_create.
+ *     objects made by mc_kv_allocator_create and mc_prefix_index_create.
  *   - Calls that take a `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) only enqueue kernels: they never synchronise, never
  *     allocate, never copy from host.  Arguments are validated on the host
