@@ -620,3 +620,13 @@ def test_wide_scores_through_chunks_and_merge(dtype):
     _scaled_kv(w, k_gain=6.0)
     assert plan_header(w)["num_merges"] > 0
     check_attention(w)
+
+
+def test_decode_over_a_128k_context():
+    # one new token over 131071 cached ones (2048 KV tiles, cut into many chunks) next to a short
+    # sequence: large tile indices, many partial rows per token
+    n = 131072
+    w = small_workload(650, mi.BF16, 32, 8, [n, 40], [n - 1, 39])
+    h = plan_header(w)
+    assert h["num_merges"] >= 1 and h["num_items"] > 8, h
+    check_attention(w)
