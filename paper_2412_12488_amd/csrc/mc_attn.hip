@@ -175,6 +175,25 @@ __device__ int block_exclusive_scan(int v, int* lds, int* total) {
   return before + incl - v;
 }
 
+// Block-wide sum of one value per thread, to every thread: butterfly inside each wavefront, the
+// 16 wavefront sums through LDS (lds holds 2 x 16 ints).
+__device__ long long block_sum(long long v, int* lds) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  __syncthreads();               // earlier readers of lds are done
+  if (lane == 0) {
+    lds[2 * wave] = (int)(v & 0xffffffffll);
+    lds[2 * wave + 1] = (int)(v >> 32);
+  }
+  __syncthreads();
+  long long all = 0;
+#pragma unroll
+  for (int w = 0; w < kPlanThreads / 64; ++w)
+    all += ((long long)lds[2 * w + 1] << 32) | (unsigned int)lds[2 * w];
+  return all;
+}
+
 // Block-wide inclusive running maximum of one value per thread.
 __device__ int block_inclusive_max_scan(int v, int* lds) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -200,9 +219,9 @@ __device__ int block_inclusive_max_scan(int v, int* lds) {
 // and orders the items by decreasing number of KV tiles (longest first), so that the tail of
 // the launch is made of short items.
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
-  __shared__ int scan[kPlanThreads / 64];   // wavefront totals of the block scans
+  __shared__ int scan[2 * kPlanThreads / 64];   // wavefront totals of the block scans and sums
   __shared__ int hist[kBuckets];
-  __shared__ int s_err, s_maxcost, s_part_tokens;
+  __shared__ int s_err, s_maxcost;
   // per-sequence arrays of batches that fit: the searches and tile look-ups below stay in LDS
   __shared__ int s_cu[kCuTilesInLds + 1], s_cuq[kCuTilesInLds + 1], s_beg[kCuTilesInLds],
       s_cup[kCuTilesInLds + 1];
@@ -216,9 +235,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   // many tiles of it are taken
   __shared__ uint8_t s_tailflag[kTailTilesMax];
   __shared__ int s_tail_bucket, s_tail_take, s_tail_taken;
-  __shared__ unsigned long long s_cost;
   const int t = threadIdx.x;
-  if (t == 0) { s_err = 0; s_maxcost = 1; s_cost = 0; s_part_tokens = 0; }
+  if (t == 0) { s_err = 0; s_maxcost = 1; }
   for (int i = t; i < kBuckets; i += kPlanThreads) hist[i] = 0;
   const bool cu_in_lds = a.batch <= kCuTilesInLds;
   if (cu_in_lds) {
@@ -328,9 +346,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   if (try_groups) {
     for (int i = t; i < a.batch; i += kPlanThreads) { s_common[i] = 0; s_gp[i] = 0; s_glead[i] = -1; s_gsize[i] = 0; }
     __syncthreads();
-    // pages in common between s and s+1, among the whole pages cached by both (one wavefront a pair)
+    // pages in common between s and s+1, among the whole pages cached by both.  First every
+    // pair at once, one thread each: unrelated sequences differ in their first page and are
+    // done (s_common = 1 marks a pair that is not).  Then one wavefront a remaining pair.
+    constexpr int kMinPages = kMinSharedTiles * kBN / kPage;
+    if (t + 1 < a.batch && s_cuq[t + 1] - s_cuq[t] == 1 && s_cuq[t + 2] - s_cuq[t + 1] == 1 &&
+        min(s_beg[t], s_beg[t + 1]) / kPage >= kMinPages &&
+        a.page_table[s_cup[t]] == a.page_table[s_cup[t + 1]])
+      s_common[t] = 1;
+    __syncthreads();
     for (int sq = t >> 6; sq + 1 < a.batch; sq += kPlanThreads >> 6) {
-      if (s_cuq[sq + 1] - s_cuq[sq] != 1 || s_cuq[sq + 2] - s_cuq[sq + 1] != 1) continue;
+      if (s_common[sq] == 0) continue;
       const int lim = min(s_beg[sq], s_beg[sq + 1]) / kPage;
       const int pa = s_cup[sq], pb = s_cup[sq + 1];
       int common = 0;
@@ -345,7 +371,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     }
     __syncthreads();
     // runs of decode rows linked by enough common pages, cut into groups of at most tile_tokens
-    constexpr int kMinPages = kMinSharedTiles * kBN / kPage;
     const bool mine = t < a.batch;
     const bool dec = mine && s_cuq[t + 1] - s_cuq[t] == 1;
     auto linked = [&](int sq) {   // sq and sq+1 sit in one run
@@ -407,14 +432,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     return (ns > 1 || x.pt > 0 ? ns * x.ntok : 0) + (x.gm ? grp_splits(x, L) * x.gm : 0);
   };
   auto total_part_rows = [&](int L) {   // block-wide
-    int rows = 0;
+    long long rows = 0;
     for (int i = t; i < total_tiles; i += kPlanThreads) rows += part_rows(locate(i), L);
-    __syncthreads();
-    if (t == 0) s_part_tokens = 0;
-    __syncthreads();
-    atomicAdd(&s_part_tokens, rows);
-    __syncthreads();
-    return s_part_tokens;
+    return block_sum(rows, scan);
   };
 
   // 4. chunk length.  No cutting when the q tiles alone give the GPU kRoundsWanted rounds of
@@ -422,15 +442,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   //    below kMinChunkTiles, doubled until the partial rows fit the workspace.
   int L = 0;
   if ((int64_t)total_tiles * a.hkv < (int64_t)kRoundsWanted * a.slots) {
-    unsigned long long cost = 0;
+    long long cost = 0;
     for (int i = t; i < total_tiles; i += kPlanThreads) {
       const Tile x = locate(i);
       cost += x.T - x.pt + (x.gm ? x.pt : 0);
     }
-    atomicAdd(&s_cost, cost);
-    __syncthreads();
-    const long long want = (long long)((s_cost * a.hkv + (unsigned long long)kItemsPerSlot * a.slots - 1) /
-                                       ((unsigned long long)kItemsPerSlot * a.slots));
+    cost = block_sum(cost, scan);
+    const long long want =
+        (cost * a.hkv + (long long)kItemsPerSlot * a.slots - 1) / ((long long)kItemsPerSlot * a.slots);
     L = want < kMinChunkTiles ? kMinChunkTiles : want > (1 << 28) ? (1 << 28) : (int)want;
     L = (L + 1) & ~1;
     for (;;) {
