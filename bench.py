@@ -382,6 +382,24 @@ def main():
     ms = timed(lambda: mc.mc_kv_append(desc_a, 0, k_new, v_new, B, total_q, cu_q, begin, table,
                                        cu_pages))
     copy["append_GBps"] = round(2 * new_bytes / ms / 1e6, 1)
+    # mark_send: the new range also goes to a transfer buffer, in the append's pass (3 x payload
+    # moved) or by a pack of the new range after the append (4 x payload moved)
+    new_off = torch.from_numpy((np.concatenate([[0], np.cumsum(w.n - w.b)[:-1]]).astype(np.int64)
+                                * w.token_bytes)).to(dev)
+    new_buf = torch.empty(max(total_q, 1) * 2 * Hkv * D, dtype=torch.int16, device=dev)
+    d_b, d_n = up(w.b.astype(np.int32)), up(w.n.astype(np.int32))
+    new_pages_max = int(max(-(-int(n) // 16) - int(b) // 16 for n, b in zip(w.n, w.b)))
+    ms_fused = timed(lambda: mc.mc_kv_append_send(desc_a, 0, k_new, v_new, B, total_q, cu_q, begin,
+                                                  table, cu_pages, 0, d_b, d_n, new_off, new_buf))
+
+    def append_then_pack():
+        mc.mc_kv_append(desc_a, 0, k_new, v_new, B, total_q, cu_q, begin, table, cu_pages)
+        mc.mc_kv_pack_batch(desc_a, 0, 1, B, table, cu_pages, d_b, d_n, new_off, new_pages_max,
+                            new_buf)
+    ms_two = timed(append_then_pack)
+    copy["append_send_us"] = round(ms_fused * 1e3, 1)
+    copy["append_then_pack_us"] = round(ms_two * 1e3, 1)
+    copy["append_send_GBps"] = round(3 * new_bytes / ms_fused / 1e6, 1)
 
     def pack_all():
         for s in range(B):

@@ -130,6 +130,30 @@ mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer,
                        const int32_t* cu_pages /* device [batch+1] */,
                        void* stream);
 
+/* mark_send (Sec. 3.4: KV marked for sending leaves while the computation goes
+ * on, layer by layer, Sec. 3.5): mc_kv_append, and in the same pass the tokens of
+ * the new range that lie in the marked range [s0[s], s1[s]) of their sequence
+ * are written to the sequence's slice of a transfer buffer as well - the bytes
+ * mc_kv_pack_batch(pool, send_layer_begin, ..., s0, s1, buf_offset, ...) would
+ * write for this layer and these tokens, without reading them back from the
+ * pages.  The part of a marked range that was cached before ([s0, begin)) is
+ * mc_kv_pack_batch's.  s0[s] < 0 or s0[s] >= s1[s] marks nothing for sequence s.
+ * send_layer_begin: first layer of the buffer's layout (<= layer, else
+ * MC_ERR_RANGE); the other errors are those of mc_kv_append and mc_kv_pack_batch. */
+mc_status mc_kv_append_send(const mc_pool_desc* pool, int32_t layer,
+                            const void* k_new /* device [total_q][Hkv][D] */,
+                            const void* v_new /* device [total_q][Hkv][D] */,
+                            int32_t batch, int32_t total_q,
+                            const int32_t* cu_q /* device [batch+1] */,
+                            const int32_t* begin /* device [batch] */,
+                            const int32_t* page_table /* device */,
+                            const int32_t* cu_pages /* device [batch+1] */,
+                            int32_t send_layer_begin,
+                            const int32_t* s0 /* device [batch] */,
+                            const int32_t* s1 /* device [batch] */,
+                            const int64_t* buf_offset /* device [batch], bytes */,
+                            void* sendbuf /* device */, void* stream);
+
 /* ---- attention of the new range over the paged cache -----------------------
  * For sequence s, new token at position i in [begin[s], begin[s]+q_s), head h:
  *   out[i,h,:] = sum_j softmax_j(scale * q[i,h].k[j,h/G]) * v[j,h/G,:],  j in [0, i]

@@ -16,7 +16,7 @@ EXPORTS = [
     "mc_status_string", "mc_abi_version",
     "mc_kv_allocator_create", "mc_kv_allocator_destroy", "mc_kv_alloc_pages", "mc_kv_free_pages",
     "mc_kv_allocator_num_free", "mc_kv_check_page_table",
-    "mc_kv_append", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_check",
+    "mc_kv_append", "mc_kv_append_send", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_check",
     "mc_prefix_prefill_attn", "mc_kv_pack_range", "mc_kv_unpack_range",
     "mc_kv_pack_batch", "mc_kv_unpack_batch",
     "mc_mfma_probe_operand_bytes", "mc_mfma_probe",
@@ -67,6 +67,8 @@ def lib():
     L.mc_kv_allocator_num_free.argtypes = [vp, C.POINTER(i32)]
     L.mc_kv_check_page_table.argtypes = [C.POINTER(i32), i64, i32]
     L.mc_kv_append.argtypes = [pd, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+    L.mc_kv_append_send.argtypes = [pd, i32, vp, vp, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp,
+                                    vp]
     L.mc_attn_workspace_size.argtypes = [i32, i32, i32, i32]
     L.mc_attn_workspace_size.restype = sz
     L.mc_attn_plan.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -173,6 +175,15 @@ def mc_kv_append(pool: mc_pool_desc, layer, k_new, v_new, batch, total_q, cu_q, 
     _check(lib().mc_kv_append(C.byref(pool), layer, _ptr(k_new), _ptr(v_new), batch, total_q,
                               _ptr(cu_q), _ptr(begin), _ptr(page_table), _ptr(cu_pages),
                               _stream(stream)), "mc_kv_append")
+
+
+def mc_kv_append_send(pool: mc_pool_desc, layer, k_new, v_new, batch, total_q, cu_q, begin,
+                      page_table, cu_pages, send_layer_begin, s0, s1, buf_offset, sendbuf,
+                      stream=None):
+    _check(lib().mc_kv_append_send(C.byref(pool), layer, _ptr(k_new), _ptr(v_new), batch, total_q,
+                                   _ptr(cu_q), _ptr(begin), _ptr(page_table), _ptr(cu_pages),
+                                   send_layer_begin, _ptr(s0), _ptr(s1), _ptr(buf_offset),
+                                   _ptr(sendbuf), _stream(stream)), "mc_kv_append_send")
 
 
 def mc_attn_workspace_size(batch, total_q, num_q_heads, num_kv_heads) -> int:

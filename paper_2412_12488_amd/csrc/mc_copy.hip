@@ -103,9 +103,17 @@ struct AppendArgs {
   int64_t page_stride;
   int32_t num_pages;
   int32_t batch, total_q, hkv;
+  // marked for sending (kSend): tokens [s0_of[s], s1_of[s]) of sequence s also go to its slice of
+  // the transfer buffer, laid out as pack writes it
+  char* buf;
+  const int32_t* s0_of;
+  const int32_t* s1_of;
+  const int64_t* buf_offset;
+  int32_t layer_rel;       // layer - first layer of the transfer buffer
 };
 
 // grid.x: 2 * (chunk of 16 consecutive tokens of the ragged new-token stream) + (0 = K, 1 = V)
+template <bool kSend>
 __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a) {
   const int g = (blockIdx.x >> 1) * kPage + (threadIdx.x >> 4);
   const int lane16 = threadIdx.x & 15;
@@ -130,6 +138,15 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a) {
   const char* src = (kv ? a.v_new : a.k_new) + (int64_t)g * a.hkv * kRowBytes + lane16 * 16;
   char* dst = a.pool_layer + page * a.page_stride + (int64_t)kv * a.hkv * kHeadPageBytes +
               (pos % kPage) * kRowBytes + lane16 * 16;
+  // the token's row in the transfer buffer, if it is marked: [layer][K|V][token - s0][head][D]
+  char* sent = nullptr;
+  if (kSend) {
+    const int s0 = a.s0_of[s], s1 = a.s1_of[s];
+    const int64_t off = a.buf_offset[s];
+    if (s0 >= 0 && pos >= s0 && pos < s1 && off >= 0 && (off & 15) == 0)
+      sent = a.buf + off +
+             ((int64_t)(a.layer_rel * 2 + kv) * (s1 - s0) + (pos - s0)) * a.hkv * kRowBytes + lane16 * 16;
+  }
   for (int h0 = 0; h0 < a.hkv; h0 += kMaxHeadsInFlight) {
     u32x4 r[kMaxHeadsInFlight];
 #pragma unroll
@@ -142,6 +159,12 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a) {
       if (h0 + i < a.hkv)
         __builtin_nontemporal_store(
             r[i], reinterpret_cast<u32x4*>(dst + (int64_t)(h0 + i) * kHeadPageBytes));
+    if (kSend && sent) {
+#pragma unroll
+      for (int i = 0; i < kMaxHeadsInFlight; ++i)
+        if (h0 + i < a.hkv)
+          __builtin_nontemporal_store(r[i], reinterpret_cast<u32x4*>(sent + (h0 + i) * kRowBytes));
+    }
   }
 }
 
@@ -260,17 +283,23 @@ mc_status mc_kv_unpack_batch(const mc_pool_desc* pool, int32_t layer_begin, int3
                           buf_offset, max_range_pages, const_cast<void*>(sendbuf), stream);
 }
 
-mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer, const void* k_new,
-                       const void* v_new, int32_t batch, int32_t total_q, const int32_t* cu_q,
-                       const int32_t* begin, const int32_t* page_table, const int32_t* cu_pages,
-                       void* stream) {
+static mc_status append_impl(const mc_pool_desc* pool, int32_t layer, const void* k_new,
+                             const void* v_new, int32_t batch, int32_t total_q,
+                             const int32_t* cu_q, const int32_t* begin, const int32_t* page_table,
+                             const int32_t* cu_pages, bool send, int32_t send_layer_begin,
+                             const int32_t* s0, const int32_t* s1, const int64_t* buf_offset,
+                             void* sendbuf, void* stream) {
   mc_status st = mc::check_pool(pool);
   if (st != MC_OK) return st;
   if (layer < 0 || layer >= pool->num_layers) return MC_ERR_RANGE;
+  if (send && (send_layer_begin < 0 || send_layer_begin > layer)) return MC_ERR_RANGE;
   if (batch < 0 || total_q < 0) return MC_ERR_INVALID;
   if (batch == 0 || total_q == 0) return MC_OK;
   if (!k_new || !v_new || !cu_q || !begin || !page_table || !cu_pages) return MC_ERR_INVALID;
   if (!mc::aligned16(k_new) || !mc::aligned16(v_new)) return MC_ERR_INVALID;
+  if (send && (!s0 || !s1 || !buf_offset || !sendbuf || !mc::aligned16(sendbuf) ||
+               (reinterpret_cast<uintptr_t>(buf_offset) & 7u)))
+    return MC_ERR_INVALID;
   AppendArgs a;
   a.pool_layer = static_cast<char*>(pool->base) + layer * mc::layer_stride_bytes(pool);
   a.k_new = static_cast<const char*>(k_new);
@@ -284,9 +313,36 @@ mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer, const void* k_ne
   a.batch = batch;
   a.total_q = total_q;
   a.hkv = pool->num_kv_heads;
+  a.buf = static_cast<char*>(sendbuf);
+  a.s0_of = s0;
+  a.s1_of = s1;
+  a.buf_offset = buf_offset;
+  a.layer_rel = send ? layer - send_layer_begin : 0;
   dim3 grid(2u * ((total_q + kPage - 1) / kPage));
-  hipLaunchKernelGGL(append_kernel, grid, dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (send)
+    hipLaunchKernelGGL(append_kernel<true>, grid, dim3(kThreads), 0, hs, a);
+  else
+    hipLaunchKernelGGL(append_kernel<false>, grid, dim3(kThreads), 0, hs, a);
   return mc::launch_status();
+}
+
+mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer, const void* k_new,
+                       const void* v_new, int32_t batch, int32_t total_q, const int32_t* cu_q,
+                       const int32_t* begin, const int32_t* page_table, const int32_t* cu_pages,
+                       void* stream) {
+  return append_impl(pool, layer, k_new, v_new, batch, total_q, cu_q, begin, page_table, cu_pages,
+                     false, 0, nullptr, nullptr, nullptr, nullptr, stream);
+}
+
+mc_status mc_kv_append_send(const mc_pool_desc* pool, int32_t layer, const void* k_new,
+                            const void* v_new, int32_t batch, int32_t total_q,
+                            const int32_t* cu_q, const int32_t* begin, const int32_t* page_table,
+                            const int32_t* cu_pages, int32_t send_layer_begin, const int32_t* s0,
+                            const int32_t* s1, const int64_t* buf_offset, void* sendbuf,
+                            void* stream) {
+  return append_impl(pool, layer, k_new, v_new, batch, total_q, cu_q, begin, page_table, cu_pages,
+                     true, send_layer_begin, s0, s1, buf_offset, sendbuf, stream);
 }
 
 }  // extern "C"

@@ -630,3 +630,59 @@ def test_decode_over_a_128k_context():
     h = plan_header(w)
     assert h["num_merges"] >= 1 and h["num_items"] > 8, h
     check_attention(w)
+
+
+def test_append_send_writes_pool_and_marked_rows():
+    """mark_send: the append of the new range also writes the marked tokens to the transfer
+    buffer, byte for byte what pack writes for them after a plain append, and nothing else."""
+    L, Hkv = 3, 8
+    lens = [300, 64, 77, 130, 40]
+    begins = [100, 0, 20, 129, 40]            # the last sequence has nothing new
+    s0 = [100, 5, 30, 129, 0]                 # whole new range / inside it / inside / one token / nothing new
+    s1 = [300, 60, 70, 130, 40]
+    s0[2], s1[2] = 10, 77                     # starts below begin: rows of [10, 20) stay untouched
+    w = small_workload(700, mi.BF16, Hkv, Hkv, lens, begins, layers=L)
+    init = canary(20, DevPool(w).elems)
+    pool, ref_pool = DevPool(w, fill=init), DevPool(w, fill=init)
+    opool = init.copy()
+    B = len(lens)
+    first_layer = 1                           # the buffer holds layers 1 and 2
+    sizes = [(L - first_layer) * 2 * (s1[i] - s0[i]) * Hkv * 128 for i in range(B)]
+    guard, offs, at = 64, [], 64
+    for n in sizes:
+        offs.append(at)
+        at += n + guard
+    raw = canary(21, at)
+    send = dev(raw)
+    db = DevBatch(w)
+    d_s0, d_s1 = dev(np.array(s0, np.int32)), dev(np.array(s1, np.int32))
+    d_off = torch.tensor([2 * o for o in offs], dtype=torch.int64, device=DEV)
+    for layer in range(L):
+        ks = np.concatenate([w.kv(s, layer)[0][begins[s]:lens[s]] for s in range(B)])
+        vs = np.concatenate([w.kv(s, layer)[1][begins[s]:lens[s]] for s in range(B)])
+        if layer >= first_layer:
+            mc.mc_kv_append_send(pool.desc, layer, dev(ks), dev(vs), db.batch, db.total_q, db.cu_q,
+                                 db.begin, db.page_table, db.cu_pages, first_layer, d_s0, d_s1,
+                                 d_off, send)
+        else:
+            gpu_append(pool, layer, dev(ks), dev(vs), db)
+        gpu_append(ref_pool, layer, dev(ks), dev(vs), db)
+        for s in range(B):
+            if lens[s] > begins[s]:
+                k, v = w.kv(s, layer)
+                oracle.append(opool, pool.shape, layer, k[begins[s]:lens[s]], v[begins[s]:lens[s]],
+                              begins[s], w.page_tables[s])
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(pool.t), opool)               # the pool: exactly a plain append
+    assert np.array_equal(bits(ref_pool.t), opool)
+    expect = raw.copy()
+    for i in range(B):
+        if s1[i] <= s0[i]:
+            continue
+        full = oracle.pack(opool, pool.shape, first_layer, L, w.page_tables[i], s0[i], s1[i])
+        lo = max(begins[i], s0[i]) - s0[i]                   # rows of tokens below begin are not new
+        hi = min(lens[i], s1[i]) - s0[i]
+        cur = expect[offs[i]:offs[i] + sizes[i]].reshape(full.shape).copy()
+        cur[:, :, lo:hi] = full[:, :, lo:hi]
+        expect[offs[i]:offs[i] + sizes[i]] = cur.ravel()
+    assert np.array_equal(bits(send), expect)                # marked rows, holes and guards

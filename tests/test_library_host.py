@@ -132,6 +132,12 @@ def test_validation_rejects_before_launch():
     assert _status(ap, ok, 0, None, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE) == mc.MC_ERR_INVALID
     assert _status(ap, ok, 0, FAKE, FAKE, 1, -1, FAKE, FAKE, FAKE, FAKE) == mc.MC_ERR_INVALID
     assert _status(ap, ok, 0, FAKE, FAKE, 1, 0, FAKE, FAKE, FAKE, FAKE) == mc.MC_OK
+    aps = mc.mc_kv_append_send
+    assert _status(aps, ok, 0, FAKE, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE, 1, FAKE, FAKE, FAKE, FAKE) == mc.MC_ERR_RANGE
+    assert _status(aps, ok, 0, FAKE, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE, 0, None, FAKE, FAKE, FAKE) == mc.MC_ERR_INVALID
+    assert _status(aps, ok, 0, FAKE, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE + 4, FAKE) == mc.MC_ERR_INVALID
+    assert _status(aps, ok, 0, FAKE, FAKE, 1, 16, FAKE, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, FAKE + 8) == mc.MC_ERR_INVALID
+    assert _status(aps, ok, 0, FAKE, FAKE, 1, 0, FAKE, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, FAKE) == mc.MC_OK
     at = mc.mc_prefix_prefill_attn
     base = [ok, 0, FAKE, 32, 1, 16, FAKE, FAKE, FAKE, FAKE, 0.0, FAKE, FAKE, FAKE, 1 << 20]
 
