@@ -250,6 +250,27 @@ mc_status mc_kv_unpack_batch(const mc_pool_desc* pool, int32_t layer_begin, int3
                              int32_t max_range_pages, const void* sendbuf /* device */,
                              void* stream);
 
+/* ---- fork_sequence (Sec. 3.4) -------------------------------------------------
+ * A new sequence that continues the first n_tokens tokens of a parent.  Its page
+ * table lists the parent's whole pages (shared, read-only for both from now on:
+ * attention and pack may read shared pages, Sec. 3.4) and, if n_tokens is not a
+ * multiple of 16, a fresh page for the partly filled last one, because each of
+ * the two sequences goes on appending at slot n_tokens % 16.
+ * mc_kv_fork_sequence (host): child_pages_out[0, ceil(n_tokens/16)) and the copy
+ * that is still to be made: slots [0, *copy_slots_out) of page *copy_src_out to
+ * page *copy_dst_out in every layer (-1, -1, 0 when no copy is needed).
+ * MC_ERR_NO_PAGES changes nothing.  The allocator does not count references:
+ * freeing a shared page while another sequence lists it is the caller's error.
+ * mc_kv_copy_page (device, asynchronous on stream): that copy, for layers
+ * [layer_begin, layer_end); no other byte of the pool is written.  Page ids
+ * outside the pool, slots outside [0, 16]: MC_ERR_RANGE; src == dst: MC_ERR_ALIAS. */
+mc_status mc_kv_fork_sequence(void* alloc, const int32_t* parent_pages /* host */,
+                              int32_t n_tokens, int32_t* child_pages_out /* host */,
+                              int32_t* copy_src_out, int32_t* copy_dst_out,
+                              int32_t* copy_slots_out);
+mc_status mc_kv_copy_page(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                          int32_t src_page, int32_t dst_page, int32_t slots, void* stream);
+
 /* ---- host arithmetic of remote_send ------------------------------------------
  * Which token ranges a sender copies, computes and sends (Sec. 3.4, the two
  * prefix-matching cases of the attention/transfer interface).  The sender's

@@ -286,3 +286,25 @@ def prep_recv(index: PrefixIndex, alloc: Allocator, prompt, end: int):
     if fresh is None:
         return None
     return pages + fresh, match_len
+
+
+# ---- fork_sequence (paper Sec. 3.4) ----
+def fork_sequence(alloc: Allocator, parent_pages, n_tokens: int, page_size: int = 16):
+    """The child's page list for the parent's first n_tokens tokens: whole pages shared, a fresh
+    page for a partly filled last one; plus the copy to make as (src page, dst page, slots), or
+    (-1, -1, 0).  None when the allocator has no page left."""
+    whole, rest = divmod(n_tokens, page_size)
+    child = [int(p) for p in parent_pages[:whole]]
+    if rest == 0:
+        return child, (-1, -1, 0)
+    fresh = alloc.take(1)
+    if fresh is None:
+        return None
+    return child + fresh, (int(parent_pages[whole]), fresh[0], rest)
+
+
+def copy_page(pool, shape: Shape, layer_begin: int, layer_end: int, src: int, dst: int,
+              slots: int) -> None:
+    """In place: slots [0, slots) of page src to page dst, K and V, every head, given layers."""
+    view = pool.reshape(shape.pool_dims())      # [layer][page][K|V][head][slot][d]
+    view[layer_begin:layer_end, dst, :, :, :slots, :] = view[layer_begin:layer_end, src, :, :, :slots, :]

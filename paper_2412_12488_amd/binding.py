@@ -22,7 +22,7 @@ EXPORTS = [
     "mc_mfma_probe_operand_bytes", "mc_mfma_probe",
     "mc_plan_remote_send", "mc_addr_compress", "mc_addr_expand",
     "mc_prefix_index_create", "mc_prefix_index_destroy", "mc_prefix_index_insert",
-    "mc_prefix_index_match", "mc_prep_recv",
+    "mc_prefix_index_match", "mc_prep_recv", "mc_kv_fork_sequence", "mc_kv_copy_page",
 ]
 
 
@@ -90,6 +90,9 @@ def lib():
     L.mc_prefix_index_insert.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(i32)]
     L.mc_prefix_index_match.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32)]
     L.mc_prep_recv.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32)]
+    L.mc_kv_fork_sequence.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32),
+                                      C.POINTER(i32), C.POINTER(i32)]
+    L.mc_kv_copy_page.argtypes = [pd, i32, i32, i32, i32, i32, vp]
     _lib = L
     return L
 
@@ -310,3 +313,19 @@ def mc_prep_recv(index, alloc, prompt, end):
     _check(lib().mc_prep_recv(index, alloc, _i32_array(prompt), end, out, C.byref(m)),
            "mc_prep_recv")
     return [out[i] for i in range(-(-end // 16))], m.value
+
+
+def mc_kv_fork_sequence(alloc, parent_pages, n_tokens):
+    """Returns (child page list, (src page, dst page, slots) of the copy still to be made)."""
+    n = -(-n_tokens // 16)
+    out = (C.c_int32 * max(n, 1))()
+    src, dst, slots = C.c_int32(-1), C.c_int32(-1), C.c_int32(0)
+    _check(lib().mc_kv_fork_sequence(alloc, _i32_array(parent_pages), n_tokens, out, C.byref(src),
+                                     C.byref(dst), C.byref(slots)), "mc_kv_fork_sequence")
+    return [out[i] for i in range(n)], (src.value, dst.value, slots.value)
+
+
+def mc_kv_copy_page(pool: mc_pool_desc, layer_begin, layer_end, src_page, dst_page, slots,
+                    stream=None):
+    _check(lib().mc_kv_copy_page(C.byref(pool), layer_begin, layer_end, src_page, dst_page, slots,
+                                 _stream(stream)), "mc_kv_copy_page")

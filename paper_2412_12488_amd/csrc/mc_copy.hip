@@ -168,6 +168,25 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a) {
   }
 }
 
+struct PageCopyArgs {
+  char* pool;
+  int64_t layer_stride, page_stride;
+  int32_t layer_begin, src_page, dst_page, slots, hkv;
+};
+
+// grid.x: 0 = K, 1 = V; grid.y: layer - layer_begin.  Slots [0, slots) of one page to another.
+__global__ __launch_bounds__(kThreads) void page_copy_kernel(PageCopyArgs a) {
+  const int slot = threadIdx.x >> 4, lane16 = threadIdx.x & 15;
+  if (slot >= a.slots) return;
+  const int64_t in_page = (int64_t)blockIdx.x * a.hkv * kHeadPageBytes + slot * kRowBytes + lane16 * 16;
+  char* layer = a.pool + (a.layer_begin + (int64_t)blockIdx.y) * a.layer_stride;
+  const char* src = layer + a.src_page * a.page_stride + in_page;
+  char* dst = layer + a.dst_page * a.page_stride + in_page;
+  for (int h = 0; h < a.hkv; ++h)
+    *reinterpret_cast<u32x4*>(dst + (int64_t)h * kHeadPageBytes) =
+        *reinterpret_cast<const u32x4*>(src + (int64_t)h * kHeadPageBytes);
+}
+
 mc_status range_copy(bool pack, const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
                      const int32_t* pages, int32_t n_table_pages, int32_t s0, int32_t s1,
                      void* sendbuf, void* stream) {
@@ -343,6 +362,32 @@ mc_status mc_kv_append_send(const mc_pool_desc* pool, int32_t layer, const void*
                             void* stream) {
   return append_impl(pool, layer, k_new, v_new, batch, total_q, cu_q, begin, page_table, cu_pages,
                      true, send_layer_begin, s0, s1, buf_offset, sendbuf, stream);
+}
+
+mc_status mc_kv_copy_page(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,
+                          int32_t src_page, int32_t dst_page, int32_t slots, void* stream) {
+  mc_status st = mc::check_pool(pool);
+  if (st != MC_OK) return st;
+  if (layer_begin < 0 || layer_end < layer_begin || layer_end > pool->num_layers)
+    return MC_ERR_RANGE;
+  if (src_page < 0 || src_page >= pool->num_pages || dst_page < 0 || dst_page >= pool->num_pages ||
+      slots < 0 || slots > kPage)
+    return MC_ERR_RANGE;
+  if (src_page == dst_page) return MC_ERR_ALIAS;
+  if (slots == 0 || layer_begin == layer_end) return MC_OK;
+  if (layer_end - layer_begin > 65535) return MC_ERR_UNSUPPORTED;
+  PageCopyArgs a;
+  a.pool = static_cast<char*>(pool->base);
+  a.layer_stride = mc::layer_stride_bytes(pool);
+  a.page_stride = mc::page_stride_bytes(pool);
+  a.layer_begin = layer_begin;
+  a.src_page = src_page;
+  a.dst_page = dst_page;
+  a.slots = slots;
+  a.hkv = pool->num_kv_heads;
+  hipLaunchKernelGGL(page_copy_kernel, dim3(2, (unsigned)(layer_end - layer_begin)), dim3(kThreads),
+                     0, static_cast<hipStream_t>(stream), a);
+  return mc::launch_status();
 }
 
 }  // extern "C"

@@ -246,4 +246,26 @@ mc_status mc_prep_recv(void* index, void* alloc, const int32_t* prompt, int32_t 
   return MC_OK;
 }
 
+mc_status mc_kv_fork_sequence(void* alloc, const int32_t* parent_pages, int32_t n_tokens,
+                              int32_t* child_pages_out, int32_t* copy_src_out,
+                              int32_t* copy_dst_out, int32_t* copy_slots_out) {
+  if (!alloc || !copy_src_out || !copy_dst_out || !copy_slots_out) return MC_ERR_INVALID;
+  if (n_tokens < 0) return MC_ERR_RANGE;
+  const int32_t whole = n_tokens / mc::kPage, rest = n_tokens % mc::kPage;
+  if (n_tokens > 0 && (!parent_pages || !child_pages_out)) return MC_ERR_INVALID;
+  *copy_src_out = *copy_dst_out = -1;
+  *copy_slots_out = 0;
+  if (rest) {   // the fork appends to a copy of the partly filled page, never to the parent's
+    int32_t fresh;
+    mc_status st = mc_kv_alloc_pages(alloc, 1, &fresh);
+    if (st != MC_OK) return st;
+    child_pages_out[whole] = fresh;
+    *copy_src_out = parent_pages[whole];
+    *copy_dst_out = fresh;
+    *copy_slots_out = rest;
+  }
+  std::copy(parent_pages, parent_pages + whole, child_pages_out);
+  return MC_OK;
+}
+
 }  // extern "C"

@@ -686,3 +686,54 @@ def test_append_send_writes_pool_and_marked_rows():
         cur[:, :, lo:hi] = full[:, :, lo:hi]
         expect[offs[i]:offs[i] + sizes[i]] = cur.ravel()
     assert np.array_equal(bits(send), expect)                # marked rows, holes and guards
+
+
+def test_fork_sequence_copies_the_partial_page_and_forks_diverge():
+    """fork_sequence (Sec. 3.4): the child shares the parent's whole pages and gets a copy of the
+    partly filled one; both then append their own next token and attend: each sees the common
+    100 tokens and only its own new one."""
+    Hq, Hkv, L, n = 32, 8, 2, 100
+    w = small_workload(710, mi.BF16, Hq, Hkv, [n + 1, n + 1], [n, n], num_pages=32, layers=L)
+    init = canary(30, DevPool(w).elems)
+    pool = DevPool(w, fill=init)
+    opool = init.copy()
+    al = mc.mc_kv_allocator_create(32)
+    parent = mc.mc_kv_alloc_pages(al, 7)                      # 100 tokens: 6 whole pages + 4 slots
+    kp = [w.kv(0, l) for l in range(L)]
+    wp = mi.Workload("p", w.seed, w.dtype, L, Hq, Hkv, 32, np.array([n]), np.array([0]),
+                     [np.array(parent, np.int32)])
+    for l in range(L):
+        gpu_append(pool, l, dev(kp[l][0][:n]), dev(kp[l][1][:n]), DevBatch(wp))
+        oracle.append(opool, pool.shape, l, kp[l][0][:n], kp[l][1][:n], 0, parent)
+    child, (src, dst, slots) = mc.mc_kv_fork_sequence(al, parent, n)
+    assert child[:6] == parent[:6] and (src, slots) == (parent[6], 4) and dst == child[6]
+    mc.mc_kv_copy_page(pool.desc, 0, L, src, dst, slots)
+    oracle.copy_page(opool, pool.shape, 0, L, src, dst, slots)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(pool.t), opool)                # the copy and nothing else
+    # both sequences append their own token 100 and attend it
+    wf = mi.Workload("f", w.seed, w.dtype, L, Hq, Hkv, 32, np.array([n + 1, n + 1]),
+                     np.array([n, n]), [np.array(parent, np.int32), np.array(child, np.int32)])
+    kc = [w.kv(1, l) for l in range(L)]
+    db = DevBatch(wf)
+    for l in range(L):
+        k_new = np.concatenate([kp[l][0][n:n + 1], kc[l][0][n:n + 1]])
+        v_new = np.concatenate([kp[l][1][n:n + 1], kc[l][1][n:n + 1]])
+        gpu_append(pool, l, dev(k_new), dev(v_new), db)
+        oracle.append(opool, pool.shape, l, kp[l][0][n:n + 1], kp[l][1][n:n + 1], n, parent)
+        oracle.append(opool, pool.shape, l, kc[l][0][n:n + 1], kc[l][1][n:n + 1], n, child)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(pool.t), opool)
+    for l in range(L):
+        q = np.concatenate([w.q(0, l), w.q(1, l)])
+        out, lse = gpu_attention(pool, l, dev(q), db)
+        for s, tab in enumerate((parent, child)):
+            ro, rl = oracle.attention(opool, pool.shape, l, np.array(tab, np.int32), q[s:s + 1],
+                                      Hq, n, n + 1)
+            assert np.max(np.abs(oracle.decode(bits(out[s:s + 1]), w.dtype) - ro)) <= O_TOL
+            assert np.max(np.abs(lse[s:s + 1].cpu().numpy() - rl)) <= LSE_TOL
+    # the child's last page holds the parent's first 4 slots and its own fifth
+    view = opool.reshape(pool.shape.pool_dims())
+    assert np.array_equal(view[:, child[6], :, :, :4], view[:, parent[6], :, :, :4])
+    assert not np.array_equal(view[:, child[6], :, :, 4], view[:, parent[6], :, :, 4])
+    mc.mc_kv_allocator_destroy(al)

@@ -285,3 +285,33 @@ def test_prefix_index_errors():
     assert L.mc_prep_recv(ix, None, None, 0, None, None) == mc.MC_ERR_INVALID
     assert mc.mc_prefix_index_match(ix, []) == (0, [])
     mc.mc_prefix_index_destroy(ix)
+
+
+def test_fork_sequence_matches_oracle():
+    al, oal = mc.mc_kv_allocator_create(12), oracle.Allocator(12)
+    parent = mc.mc_kv_alloc_pages(al, 7)
+    assert oal.take(7) == parent
+    for n in (0, 1, 16, 17, 100, 112):
+        got = mc.mc_kv_fork_sequence(al, parent, n)
+        want = oracle.fork_sequence(oal, parent, n)
+        assert got == want, (n, got, want)
+        child, (src, dst, slots) = got
+        assert child[: n // 16] == parent[: n // 16] and slots == n % 16
+        if slots:
+            assert src == parent[n // 16] and dst == child[-1] and dst not in parent
+    # 3 pages went to forks with a partly filled last page (1, 17 and 100 tokens); two are left
+    assert mc.mc_kv_allocator_num_free(al) == oal.num_free == 2
+    mc.mc_kv_fork_sequence(al, parent, 5)
+    mc.mc_kv_fork_sequence(al, parent, 5)
+    with pytest.raises(mc.McError) as e:
+        mc.mc_kv_fork_sequence(al, parent, 5)
+    assert e.value.status == mc.MC_ERR_NO_PAGES
+    assert mc.mc_kv_fork_sequence(al, parent, 32) == (parent[:2], (-1, -1, 0))    # needs no page
+    ok = _pool()
+    cp = mc.mc_kv_copy_page
+    assert _status(cp, ok, 0, 3, 1, 2, 5) == mc.MC_ERR_RANGE
+    assert _status(cp, ok, 0, 2, 8, 2, 5) == mc.MC_ERR_RANGE
+    assert _status(cp, ok, 0, 2, 1, 2, 17) == mc.MC_ERR_RANGE
+    assert _status(cp, ok, 0, 2, 1, 1, 5) == mc.MC_ERR_ALIAS
+    assert _status(cp, ok, 0, 2, 1, 2, 0) == mc.MC_OK
+    mc.mc_kv_allocator_destroy(al)
