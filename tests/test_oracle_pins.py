@@ -508,3 +508,30 @@ def test_prep_recv_oracle_allocates_only_the_unmatched_part():
     pages2, m2 = oracle.prep_recv(ix, al, prompt, 200)    # 96 tokens matched, 13 - 6 fresh
     assert m2 == 96 and pages2[:6] == pages[:6] and pages2[6:] == [7, 8, 9, 10, 11, 12, 13]
     assert oracle.prep_recv(ix, al, [9] * 64, 64) is None and al.num_free == 2   # all or nothing
+
+
+# ---- fork_sequence (Sec. 3.4) ----
+def test_fork_sequence_oracle_hand_cases():
+    al = oracle.Allocator(10)
+    parent = al.take(7)                                  # pages 0..6 hold 100 tokens
+    child, copy = oracle.fork_sequence(al, parent, 100)  # 6 whole pages, 4 slots in the seventh
+    assert child == [0, 1, 2, 3, 4, 5, 7] and copy == (6, 7, 4)
+    assert oracle.fork_sequence(al, parent, 96) == ([0, 1, 2, 3, 4, 5], (-1, -1, 0))
+    assert oracle.fork_sequence(al, parent, 0) == ([], (-1, -1, 0))
+    assert al.num_free == 2
+
+
+def test_copy_page_oracle_moves_exactly_the_slots():
+    shape = oracle.Shape(2, 4, 16, 3, 128, oracle.BF16)
+    rng = np.random.default_rng(0)
+    pool = rng.integers(0, 65536, size=shape.pool_elems(), dtype=np.uint16)
+    before = pool.copy()
+    oracle.copy_page(pool, shape, 0, 2, 1, 3, 5)
+    v, b = pool.reshape(shape.pool_dims()), before.reshape(shape.pool_dims())
+    for layer in range(2):
+        for page in range(4):
+            for kv in range(2):
+                for head in range(3):
+                    for slot in range(16):
+                        src = (1 if (page == 3 and slot < 5) else page)
+                        assert np.array_equal(v[layer, page, kv, head, slot], b[layer, src, kv, head, slot])
