@@ -735,6 +735,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const int t0 = item[2];                            // first KV tile of the item (even)
   const int part = item[4];                          // >= 0: partial result, merged afterwards
   const int gsize = item[5];                         // > 0: shared-prefix item over gsize sequences
+  // a record that cannot come from the planner (a workspace written over by something else)
+  if ((unsigned)seq >= (unsigned)a.batch || row0 < 0 || t0 < 0 || item[3] <= t0 || gsize < 0 ||
+      gsize > TOK || seq + max(gsize, 1) > a.batch)
+    return;
   const int q0 = a.cu_q[seq], q_len = a.cu_q[seq + 1] - q0, b = a.begin[seq];
   // valid tokens in this tile (>= 1), and the position of the first one.  The rows of a
   // shared-prefix item are the new tokens of gsize consecutive sequences; all of them lie
@@ -751,7 +755,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const_i32_ptr table = (const_i32_ptr)(a.page_table + a.cu_pages[seq]);
 
   // this lane's query row
-  const int r = wave * 32 + l32;                     // row in tile, head-major
+  const int r = wave * 32 + l32;                     // row in tile
   const int g = r % G, tt = r / G;                   // token-major: the rows of a short tile
   const bool row_ok = tt < ntok;                     // (a decode step's G rows) fill whole waves
   // a wavefront none of whose rows exists only helps with the copies and the barriers
