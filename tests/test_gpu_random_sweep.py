@@ -53,3 +53,70 @@ def test_random_batches(chunk):
     rng = np.random.default_rng(4000 + chunk)
     for i in range(10):
         check_attention(random_workload(10 * chunk + i, rng))
+
+
+def test_random_copies():
+    """append, batched pack and batched unpack on seeded random shapes (1..3 layers, 1..16 kv
+    heads, ragged ranges): pools and buffers byte for byte, canary bytes everywhere else."""
+    import torch
+
+    import oracle
+    import paper_2412_12488_amd as mc
+    from gpu_harness import DEV, DevBatch, DevPool, bits, dev, gpu_append
+    from test_gpu_parity import canary
+    rng = np.random.default_rng(77)
+    for case in range(30):
+        L, Hkv, dtype = int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 8, 16])), int(rng.integers(0, 2))
+        B = int(rng.integers(1, 7))
+        lens = [int(rng.integers(1, 600)) for _ in range(B)]
+        begins = [int(rng.integers(0, n + 1)) for n in lens]
+        w = small_workload(20000 + case, dtype, Hkv, Hkv, lens, begins, layers=L)
+        init = canary(case, DevPool(w).elems)
+        pool, opool = DevPool(w, fill=init), init.copy()
+        db = DevBatch(w)
+        if db.total_q:
+            for layer in range(L):
+                ks = np.concatenate([w.kv(s, layer)[0][begins[s]:lens[s]] for s in range(B)])
+                vs = np.concatenate([w.kv(s, layer)[1][begins[s]:lens[s]] for s in range(B)])
+                gpu_append(pool, layer, dev(ks), dev(vs), db)
+                for s in range(B):
+                    if lens[s] > begins[s]:
+                        k, v = w.kv(s, layer)
+                        oracle.append(opool, pool.shape, layer, k[begins[s]:lens[s]],
+                                      v[begins[s]:lens[s]], begins[s], w.page_tables[s])
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(pool.t), opool), case
+        s0 = [int(rng.integers(0, n + 1)) for n in lens]
+        s1 = [int(rng.integers(a, n + 1)) for a, n in zip(s0, lens)]
+        lb = int(rng.integers(0, L))
+        le = int(rng.integers(lb, L + 1))
+        sizes = [(le - lb) * 2 * (b - a) * Hkv * 128 for a, b in zip(s0, s1)]
+        offs, at = [], 64
+        for n in sizes:
+            offs.append(at)
+            at += n + 64 + (-n % 8)
+        raw = canary(case + 1, at)
+        send = dev(raw)
+        d_s0, d_s1 = dev(np.array(s0, np.int32)), dev(np.array(s1, np.int32))
+        d_off = torch.tensor([2 * o for o in offs], dtype=torch.int64, device=DEV)
+        max_pages = max(((b - 1) // 16 - a // 16 + 1) if b > a else 0 for a, b in zip(s0, s1))
+        mc.mc_kv_pack_batch(pool.desc, lb, le, B, db.page_table, db.cu_pages, d_s0, d_s1, d_off,
+                            max_pages, send)
+        torch.cuda.synchronize()
+        expect, refs = raw.copy(), []
+        for i in range(B):
+            refs.append(oracle.pack(opool, pool.shape, lb, le, w.page_tables[i], s0[i], s1[i]))
+            expect[offs[i]:offs[i] + sizes[i]] = refs[i].ravel()
+        assert np.array_equal(bits(send), expect), case
+        init_b = canary(case + 2, pool.elems)
+        pool_b = DevPool(w, fill=init_b)
+        tables_b = mi.scatter_page_tables(mi.rng_for(case, 5), w.num_pages, w.n)
+        wb = mi.Workload("b", w.seed, w.dtype, L, Hkv, Hkv, w.num_pages, w.n, w.b, tables_b)
+        dbb = DevBatch(wb)
+        mc.mc_kv_unpack_batch(pool_b.desc, lb, le, B, dbb.page_table, dbb.cu_pages, d_s0, d_s1,
+                              d_off, max_pages, send)
+        torch.cuda.synchronize()
+        ob = init_b.copy()
+        for i in range(B):
+            oracle.unpack(ob, pool.shape, lb, le, tables_b[i], s0[i], s1[i], refs[i])
+        assert np.array_equal(bits(pool_b.t), ob), case
