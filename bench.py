@@ -179,9 +179,19 @@ def decode_step_latency(name, iters=50):
             step()
     torch.cuda.current_stream().wait_stream(side)
     replay = timed(graph.replay)
+
+    # the same step when the plan was made once for many steps ahead (mc_attn_plan_ahead)
+    mc.mc_attn_plan_ahead(desc, Hq, w.batch, tq, cu_q, begin, table, cu_pages, 0, ws, wsb)
+
+    def step_planned():
+        mc.mc_kv_append(desc, 0, k, v, w.batch, tq, cu_q, begin, table, cu_pages)
+        mc.mc_prefix_prefill_attn(desc, 0, q, Hq, w.batch, tq, cu_q, begin, table, cu_pages, 0.0,
+                                  out, lse, ws, wsb)
+    planned = timed(step_planned)
     del pool, q, k, v, out, lse, ws, graph
     torch.cuda.empty_cache()
-    return {"eager_us": round(eager, 1), "graph_us": round(replay, 1)}
+    return {"eager_us": round(eager, 1), "graph_us": round(replay, 1),
+            "plan_reused_us": round(planned, 1)}
 
 
 def main():

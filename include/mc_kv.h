@@ -192,6 +192,18 @@ mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t ba
                        const int32_t* page_table /* device */,
                        const int32_t* cu_pages /* device [batch+1] */,
                        void* workspace /* device */, size_t workspace_bytes, void* stream);
+/* The same plan, made to last for several decode steps: it stays valid while cu_q
+ * is unchanged and every sequence's begin has grown by at most ahead_tokens since
+ * the plan (begin is read again by every attention call; the page-table entries
+ * of the tokens to come must already be in place: they are validated here, and
+ * a table too short for begin + q + ahead_tokens is MC_ERR_RANGE at the check).
+ * Work is still cut and ordered for the lengths at planning time.
+ * ahead_tokens < 0 or > 2^20: MC_ERR_RANGE. */
+mc_status mc_attn_plan_ahead(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
+                             int32_t total_q, const int32_t* cu_q, const int32_t* begin,
+                             const int32_t* page_table, const int32_t* cu_pages,
+                             int32_t ahead_tokens, void* workspace /* device */,
+                             size_t workspace_bytes, void* stream);
 /* Synchronises `stream` and reports what the plan kernel found: MC_OK, or
  * MC_ERR_RANGE if an offset array is not monotone, a sequence's table is too
  * short for begin+q tokens, or a page id is outside the pool (then the work

@@ -16,7 +16,7 @@ EXPORTS = [
     "mc_status_string", "mc_abi_version",
     "mc_kv_allocator_create", "mc_kv_allocator_destroy", "mc_kv_alloc_pages", "mc_kv_free_pages",
     "mc_kv_allocator_num_free", "mc_kv_check_page_table",
-    "mc_kv_append", "mc_kv_append_send", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_check",
+    "mc_kv_append", "mc_kv_append_send", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_ahead", "mc_attn_plan_check",
     "mc_prefix_prefill_attn", "mc_kv_pack_range", "mc_kv_unpack_range",
     "mc_kv_pack_batch", "mc_kv_unpack_batch",
     "mc_mfma_probe_operand_bytes", "mc_mfma_probe",
@@ -72,6 +72,7 @@ def lib():
     L.mc_attn_workspace_size.argtypes = [i32, i32, i32, i32]
     L.mc_attn_workspace_size.restype = sz
     L.mc_attn_plan.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.mc_attn_plan_ahead.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, i32, vp, sz, vp]
     L.mc_attn_plan_check.argtypes = [vp, vp]
     L.mc_prefix_prefill_attn.argtypes = [pd, i32, vp, i32, i32, i32, vp, vp, vp, vp, C.c_float,
                                          vp, vp, vp, sz, vp]
@@ -198,6 +199,14 @@ def mc_attn_plan(pool: mc_pool_desc, num_q_heads, batch, total_q, cu_q, begin, p
     _check(lib().mc_attn_plan(C.byref(pool), num_q_heads, batch, total_q, _ptr(cu_q), _ptr(begin),
                               _ptr(page_table), _ptr(cu_pages), _ptr(workspace), workspace_bytes,
                               _stream(stream)), "mc_attn_plan")
+
+
+def mc_attn_plan_ahead(pool: mc_pool_desc, num_q_heads, batch, total_q, cu_q, begin, page_table,
+                       cu_pages, ahead_tokens, workspace, workspace_bytes, stream=None):
+    _check(lib().mc_attn_plan_ahead(C.byref(pool), num_q_heads, batch, total_q, _ptr(cu_q),
+                                    _ptr(begin), _ptr(page_table), _ptr(cu_pages), ahead_tokens,
+                                    _ptr(workspace), workspace_bytes, _stream(stream)),
+           "mc_attn_plan_ahead")
 
 
 def mc_attn_plan_check(workspace, stream=None):

@@ -149,6 +149,7 @@ struct PlanArgs {
   int32_t batch, total_q, tile_tokens, num_pages, max_tiles, max_items, part_cap;
   int32_t hkv, slots;   // kv heads; workgroups the GPU runs at a time
   int32_t allow_groups; // look for decode rows of neighbouring sequences that share a prefix
+  int32_t ahead;        // tokens every sequence's begin may still grow by while the plan is in use
 };
 
 // Block-wide exclusive scan of one value per thread (kPlanThreads threads): a shuffle scan
@@ -258,7 +259,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     const int np = a.cu_pages[s + 1] - a.cu_pages[s];
     if (q < 0 || b < 0 || np < 0 || a.cu_q[s] < 0 || a.cu_q[s + 1] > a.total_q) { err = 1; continue; }
     if (q == 0) continue;
-    const int64_t end = (int64_t)b + q;
+    const int64_t end = (int64_t)b + q + a.ahead;
     if ((end + kPage - 1) / kPage > np) { err = 1; continue; }
     my_tiles += (q + a.tile_tokens - 1) / a.tile_tokens;
     maxcost = max(maxcost, (int)((end + kBN - 1) / kBN));
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       for (int k = 0; k < 4; ++k) {
         const int s = s4 + k;
         const int q = s < a.batch ? s_cuq[s + 1] - s_cuq[s] : 0;
-        need[k] = q > 0 ? (s_beg[s] + q + kPage - 1) / kPage : 0;
+        need[k] = q > 0 ? (s_beg[s] + q + a.ahead + kPage - 1) / kPage : 0;
         p0[k] = s < a.batch ? s_cup[s] : 0;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   for (int s = t >> 6; !cu_in_lds && s < a.batch; s += kPlanThreads >> 6) {
     const int q = a.cu_q[s + 1] - a.cu_q[s];
     if (q == 0) continue;
-    const int need = (a.begin[s] + q + kPage - 1) / kPage, p0 = a.cu_pages[s];
+    const int need = (a.begin[s] + q + a.ahead + kPage - 1) / kPage, p0 = a.cu_pages[s];
     // eight independent loads per lane and trip: the loop is bound by memory latency
     for (int i = t & 63; i < need; i += 64 * 8) {
       int32_t pg[8];
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     const int q = cu_in_lds ? s_cuq[lo + 1] - s_cuq[lo] : a.cu_q[lo + 1] - a.cu_q[lo];
     const int b = cu_in_lds ? s_beg[lo] : a.begin[lo];
     x.ntok = min(a.tile_tokens, q - x.row0);
-    x.T = (b + x.row0 + x.ntok + kBN - 1) / kBN;
+    x.T = (b + x.row0 + x.ntok + a.ahead + kBN - 1) / kBN;   // room for the range to move up
     x.dmax = ((b + x.row0) / kBN) & ~1;
     x.pt = groups ? s_gp[lo] : 0;
     x.gm = groups && s_glead[lo] == lo ? s_gsize[lo] : 0;
@@ -1203,6 +1204,16 @@ mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t ba
                        int32_t total_q, const int32_t* cu_q, const int32_t* begin,
                        const int32_t* page_table, const int32_t* cu_pages, void* workspace,
                        size_t workspace_bytes, void* stream) {
+  return mc_attn_plan_ahead(pool, num_q_heads, batch, total_q, cu_q, begin, page_table, cu_pages,
+                            0, workspace, workspace_bytes, stream);
+}
+
+mc_status mc_attn_plan_ahead(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
+                             int32_t total_q, const int32_t* cu_q, const int32_t* begin,
+                             const int32_t* page_table, const int32_t* cu_pages,
+                             int32_t ahead_tokens, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  if (ahead_tokens < 0 || ahead_tokens > (1 << 20)) return MC_ERR_RANGE;
   int G = 0;
   mc_status st = check_attn_shape(pool, num_q_heads, batch, total_q, &G);
   if (st != MC_OK) return st;
@@ -1235,6 +1246,7 @@ mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t ba
   a.allow_groups = may_group(w, total_q, kBM / G);
   a.max_items = item_bound(w, a.hkv, a.slots, a.allow_groups);
   a.part_cap = w.part_cap;
+  a.ahead = ahead_tokens;
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0,
                      static_cast<hipStream_t>(stream), a);
   return mc::launch_status();

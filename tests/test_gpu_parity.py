@@ -737,3 +737,61 @@ def test_fork_sequence_copies_the_partial_page_and_forks_diverge():
     assert np.array_equal(view[:, child[6], :, :, :4], view[:, parent[6], :, :, :4])
     assert not np.array_equal(view[:, child[6], :, :, 4], view[:, parent[6], :, :, 4])
     mc.mc_kv_allocator_destroy(al)
+
+
+def test_one_plan_for_many_decode_steps():
+    """mc_attn_plan_ahead: a plan made once serves decode step after decode step while the
+    sequences grow (begin is read again by every attention call), up to the number of tokens it
+    was made for; the page tables already list the pages of the tokens to come."""
+    steps, Hq, Hkv = 70, 32, 8
+    start = [1000, 63, 1, 2047, 500]                      # lengths before the first step
+    final = [n + steps for n in start]
+    w_full = small_workload(720, mi.BF16, Hq, Hkv, final, [0] * len(start))   # tables for the final lengths
+    B = len(start)
+    pool = DevPool(w_full)
+    opool = oracle.new_pool(pool.shape)
+    kv = [w_full.kv(s) for s in range(B)]
+    # the contexts before the first step
+    w0 = w_full.with_ranges(np.zeros(B, dtype=np.int64), np.array(start))
+    gpu_append(pool, 0, dev(np.concatenate([kv[s][0][:start[s]] for s in range(B)])),
+               dev(np.concatenate([kv[s][1][:start[s]] for s in range(B)])), DevBatch(w0))
+    for s in range(B):
+        oracle.append(opool, pool.shape, 0, kv[s][0][:start[s]], kv[s][1][:start[s]], 0,
+                      w_full.page_tables[s])
+    # one plan at the lengths of step 0, good for `steps` more tokens
+    w_step = w_full.with_ranges(np.array(start), np.array(start) + 1)
+    db = DevBatch(w_step)
+    ws_bytes = mc.mc_attn_workspace_size(B, B, Hq, Hkv)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    mc.mc_attn_plan_ahead(pool.desc, Hq, B, B, db.cu_q, db.begin, db.page_table, db.cu_pages, steps,
+                          ws, ws_bytes)
+    mc.mc_attn_plan_check(ws)
+    out = torch.zeros((B, Hq, 128), dtype=torch.int16, device=DEV)
+    lse = torch.zeros((B, Hq), dtype=torch.float32, device=DEV)
+    q_all = [w_full.q(s) for s in range(B)]               # one query row per position
+    for t in range(steps):
+        pos = [n + t for n in start]
+        begin = dev(np.array(pos, dtype=np.int32))        # the sequences have grown by t tokens
+        k_new = np.concatenate([kv[s][0][pos[s]:pos[s] + 1] for s in range(B)])
+        v_new = np.concatenate([kv[s][1][pos[s]:pos[s] + 1] for s in range(B)])
+        q = np.concatenate([q_all[s][pos[s]:pos[s] + 1] for s in range(B)])
+        mc.mc_kv_append(pool.desc, 0, dev(k_new), dev(v_new), B, B, db.cu_q, begin, db.page_table,
+                        db.cu_pages)
+        mc.mc_prefix_prefill_attn(pool.desc, 0, dev(q), Hq, B, B, db.cu_q, begin, db.page_table,
+                                  db.cu_pages, 0.0, out, lse, ws, ws_bytes)
+        for s in range(B):
+            oracle.append(opool, pool.shape, 0, k_new[s:s + 1], v_new[s:s + 1], pos[s],
+                          w_full.page_tables[s])
+        if t % 9 == 0 or t == steps - 1:
+            torch.cuda.synchronize()
+            for s in range(B):
+                ro, rl = oracle.attention(opool, pool.shape, 0, w_full.page_tables[s], q[s:s + 1], Hq,
+                                          pos[s], pos[s] + 1)
+                assert np.max(np.abs(oracle.decode(bits(out[s:s + 1]), w_full.dtype) - ro)) <= O_TOL, (t, s)
+                assert np.max(np.abs(lse[s:s + 1].cpu().numpy() - rl)) <= LSE_TOL, (t, s)
+    # a table too short for the tokens to come is reported
+    mc.mc_attn_plan_ahead(pool.desc, Hq, B, B, db.cu_q, db.begin, db.page_table, db.cu_pages,
+                          steps + 64, ws, ws_bytes)
+    with pytest.raises(mc.McError) as e:
+        mc.mc_attn_plan_check(ws)
+    assert e.value.status == mc.MC_ERR_RANGE

@@ -154,6 +154,9 @@ def test_validation_rejects_before_launch():
     assert attn({14: 16}) == mc.MC_ERR_INVALID        # workspace too small
     assert attn({11: None}) == mc.MC_ERR_INVALID
     assert attn({5: 0}) == mc.MC_OK                   # no new tokens: nothing to do
+    pa = mc.mc_attn_plan_ahead
+    assert _status(pa, ok, 32, 1, 16, FAKE, FAKE, FAKE, FAKE, -1, FAKE, 1 << 30) == mc.MC_ERR_RANGE
+    assert _status(pa, ok, 32, 1, 16, FAKE, FAKE, FAKE, FAKE, 4, FAKE, 8) == mc.MC_ERR_INVALID
     pl = mc.mc_attn_plan
     assert _status(pl, ok, 32, 1, 16, FAKE, FAKE, FAKE, FAKE, FAKE, 8) == mc.MC_ERR_INVALID
     assert _status(pl, ok, 32, 1, 16, FAKE, FAKE, FAKE, FAKE, None, 1 << 20) == mc.MC_ERR_INVALID
