@@ -428,6 +428,19 @@ def main():
         desc_b, 0, 1, B, table_b, cu_pages_b, r_s0, r_s1, send_off, max_range_pages,
         send_all)) / 1e6, 1)
     copy["payload_MiB"] = round(kv_bytes / 2**20, 1)
+    # one layer of a 1000 / 3000 / 5000-token sequence out of one pool and into another (the
+    # paper's Table 2 transfers, there with the wire): microseconds for pack + unpack
+    t2 = {}
+    for tokens in (1000, 3000, 5000):
+        pages = up(mi.rng_for(args.seed, tokens).permutation(w.num_pages)[: -(-tokens // 16)]
+                   .astype(np.int32))
+        buf = send_all[: 2 * tokens * Hkv * D]
+
+        def there_and_back():
+            mc.mc_kv_pack_range(desc_a, 0, 1, pages, int(pages.numel()), 0, tokens, buf)
+            mc.mc_kv_unpack_range(desc_b, 0, 1, pages, int(pages.numel()), 0, tokens, buf)
+        t2[str(tokens)] = round(timed(there_and_back) * 1e3, 1)
+    copy["one_layer_pack_plus_unpack_us"] = t2
     if not args.no_copy_sweep:
         # 32768 tokens x 32 layers = 4 GiB of KV between two pools (long-context transfer)
         del pool_a, pool_b, send, send_all
