@@ -89,6 +89,7 @@ struct MergeRec {
 static_assert(sizeof(MergeRec) == 32, "merge record is 32 bytes");
 
 constexpr int kCuTilesInLds = 1024;
+constexpr int kValidateInPlan = 256;  // batches up to this have their page ids checked by plan_kernel
 constexpr int kTailTilesMax = 2048;   // q tiles up to which the remainder round is looked at
 constexpr int kMinSharedTiles = 8;    // a shared prefix shorter than 512 tokens is not worth a group
 constexpr int kMinChunkTiles = 8;     // never cut a KV range into pieces shorter than 512 keys
@@ -214,6 +215,35 @@ __device__ int block_inclusive_max_scan(int v, int* lds) {
   return max(before, incl);
 }
 
+// Page ids of every needed table entry, for batches too large for the planner's one workgroup
+// to walk: one wavefront per sequence, many workgroups.  Runs after plan_kernel and, on a bad
+// id, turns its verdict into MC_ERR_RANGE with an empty work list.  (Sequences whose offsets
+// are malformed were rejected by the planner already; they are skipped here.)
+__global__ __launch_bounds__(256) void validate_pages_kernel(PlanArgs a) {
+  const int s = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (s >= a.batch || a.hdr->err != MC_OK) return;
+  const int q = a.cu_q[s + 1] - a.cu_q[s], b = a.begin[s];
+  const int p0 = a.cu_pages[s], np = a.cu_pages[s + 1] - p0;
+  if (q <= 0 || b < 0 || p0 < 0) return;
+  const int64_t need64 = ((int64_t)b + q + a.ahead + kPage - 1) / kPage;
+  if (need64 > np) return;
+  const int need = (int)need64;
+  int err = 0;
+  for (int i = lane; i < need; i += 64 * 8) {   // eight independent loads per lane and trip
+    int32_t pg[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) pg[u] = i + 64 * u < need ? a.page_table[p0 + i + 64 * u] : 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (pg[u] < 0 || pg[u] >= a.num_pages) err = 1;
+  }
+  if (__ballot(err) != 0 && lane == 0) {
+    a.hdr->num_items = 0;
+    a.hdr->num_merges = 0;
+    a.hdr->err = MC_ERR_RANGE;
+  }
+}
+
 // One workgroup.  Validates the ragged-batch arrays, cuts every sequence's new range into q
 // tiles of tile_tokens tokens, cuts long KV ranges into chunks when the launch would otherwise
 // have too few work items to fill the GPU (decode rows, short batches over long contexts),
@@ -271,11 +301,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
     return;
   }
-  // 2. page ids of every needed table entry.  Batches whose offsets sit in LDS: a wavefront
-  //    takes four sequences per trip and has up to 32 loads per lane in flight (the loop is
+  // 2. page ids of every needed table entry.  Small batches (their offsets sit in LDS): a
+  //    wavefront takes four sequences per trip and has up to 32 loads per lane in flight (the loop is
   //    bound by memory latency); entries beyond the first 512 of a sequence follow one
   //    sequence at a time.
-  if (cu_in_lds) {
+  if (a.batch <= kValidateInPlan) {
     for (int s4 = (t >> 6) * 4; s4 < a.batch; s4 += (kPlanThreads >> 6) * 4) {
       int32_t pg[4][8];
       int need[4], p0[4];
@@ -303,20 +333,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       }
     }
   }
-  for (int s = t >> 6; !cu_in_lds && s < a.batch; s += kPlanThreads >> 6) {
-    const int q = a.cu_q[s + 1] - a.cu_q[s];
-    if (q == 0) continue;
-    const int need = (a.begin[s] + q + a.ahead + kPage - 1) / kPage, p0 = a.cu_pages[s];
-    // eight independent loads per lane and trip: the loop is bound by memory latency
-    for (int i = t & 63; i < need; i += 64 * 8) {
-      int32_t pg[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) pg[u] = i + 64 * u < need ? a.page_table[p0 + i + 64 * u] : 0;
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (pg[u] < 0 || pg[u] >= a.num_pages) err = 1;
-    }
-  }
+  // (batches beyond that: validate_pages_kernel, launched after this kernel, on many workgroups)
   if (err) atomicOr(&s_err, 1);
   // 3. exclusive scan of tiles per sequence
   int total_tiles;
@@ -1249,6 +1266,9 @@ mc_status mc_attn_plan_ahead(const mc_pool_desc* pool, int32_t num_q_heads, int3
   a.ahead = ahead_tokens;
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0,
                      static_cast<hipStream_t>(stream), a);
+  if (batch > kValidateInPlan)
+    hipLaunchKernelGGL(validate_pages_kernel, dim3((batch + 3) / 4), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), a);
   return mc::launch_status();
 }
 
