@@ -795,3 +795,30 @@ def test_one_plan_for_many_decode_steps():
     with pytest.raises(mc.McError) as e:
         mc.mc_attn_plan_check(ws)
     assert e.value.status == mc.MC_ERR_RANGE
+
+
+def test_bad_page_id_in_a_large_batch_is_reported():
+    # batches of more than 256 sequences have their page ids checked by a kernel of its own
+    rng = mi.rng_for(730)
+    lens = [int(x) for x in rng.integers(1, 200, size=300)]
+    w = small_workload(731, mi.BF16, 32, 8, lens, [n - 1 for n in lens])
+    pool, db = DevPool(w), DevBatch(w)
+    ws_bytes = mc.mc_attn_workspace_size(db.batch, db.total_q, 32, 8)
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=DEV)
+    mc.mc_attn_plan(pool.desc, 32, db.batch, db.total_q, db.cu_q, db.begin, db.page_table,
+                    db.cu_pages, ws, ws_bytes)
+    mc.mc_attn_plan_check(ws)                                 # the good tables pass
+    bad = db.page_table.clone()
+    bad[int(w.cu_pages[217])] = w.num_pages                   # first page of sequence 217
+    mc.mc_attn_plan(pool.desc, 32, db.batch, db.total_q, db.cu_q, db.begin, bad, db.cu_pages, ws,
+                    ws_bytes)
+    with pytest.raises(mc.McError) as e:
+        mc.mc_attn_plan_check(ws)
+    assert e.value.status == mc.MC_ERR_RANGE
+    out = torch.full((db.total_q, 32, 128), 0x7fc1, dtype=torch.int16, device=DEV)
+    lse = torch.full((db.total_q, 32), 7.0, dtype=torch.float32, device=DEV)
+    q = torch.zeros((db.total_q, 32, 128), dtype=torch.int16, device=DEV)
+    mc.mc_prefix_prefill_attn(pool.desc, 0, q, 32, db.batch, db.total_q, db.cu_q, db.begin, bad,
+                              db.cu_pages, 0.0, out, lse, ws, ws_bytes)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0x7fc1) and torch.all(lse == 7.0)     # the failed plan launches nothing useful
