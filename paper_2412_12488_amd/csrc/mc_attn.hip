@@ -697,9 +697,16 @@ template <> constexpr bool kTryFixedRef<__bf16> = true;
 constexpr float kFixedRefSumLimit = 0x1p+60f;
 // register pairs of S(h) whose exponentials run in phase 2 of a fixed-reference half step
 #ifndef MC_PAIRS_LATE
-#define MC_PAIRS_LATE 2
+#define MC_PAIRS_LATE 4
 #endif
 constexpr int kPairsLate = MC_PAIRS_LATE;
+// MFMA slot (0..15 of a half step) after which the first of a tile's eight copies is issued in
+// the main loop; one more follows after each later slot
+#ifndef MC_COPY_SLOT0
+#define MC_COPY_SLOT0 4
+#endif
+constexpr int kCopySlot0 = MC_COPY_SLOT0;
+static_assert(kCopySlot0 >= 1 && kCopySlot0 <= 8, "eight copy slots and one for the addresses before them");
 static_assert(kPairsLate >= 0 && kPairsLate <= 4, "operand words 4..7 are read from phase 2's step 4 on");
 
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
@@ -855,11 +862,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   // not track, so every later read of it must be ordered after this wait by data dependence.
   int32_t ids_next;                       // table entries 4j+4 .. 4j+11 during tile j
   auto wait_copies_and_sync = [&]() __attribute__((always_inline)) {
-#ifdef MC_ABL_NOWAIT
-    asm volatile("s_waitcnt vmcnt(8)" : "+v"(ids_next) : : "memory");
-#else
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(ids_next) : : "memory");
-#endif
     __syncthreads();
   };
 
@@ -924,7 +927,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   //      into phase 2, whose VALU slots the row max no longer needs.
   auto half_step = [&](auto fixed_ref, int h, uint32_t k_next, bool fetch_after, uint32_t k_after,
                        uint32_t v_cur, int crow, f32x16& s_cur, f32x16& s_next,
-                       bool mask_next) __attribute__((always_inline)) {
+                       bool mask_next, auto&& slot_extra) __attribute__((always_inline)) {
     constexpr bool kFixed = decltype(fixed_ref)::value;
     constexpr int kLate = kFixed ? kPairsLate : 0;
     vec8 vf[kAhead];
@@ -963,6 +966,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
       s_next = Mfma<T>::run(kf[t % kAhead], qreg[t], t == 0 ? zero16 : s_next);
       if (t + kAhead < 8) kf[t % kAhead] = k_frag(k_next, t + kAhead);
       else vf[t % kAhead] = v_frag(v_cur, crow, t + kAhead - 8);
+      slot_extra(t);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (mask_next) mask_half(h + 1, s_next);
@@ -981,6 +985,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
       } else {
         mx = u == 0 ? fmaxf(s_next[0], s_next[1]) : max3(mx, s_next[2 * u], s_next[2 * u + 1]);
       }
+      slot_extra(8 + u);
       __builtin_amdgcn_sched_barrier(0);
     }
     if constexpr (!kFixed) mx_cur = max_across_halves(mx);
@@ -989,35 +994,62 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   // ---- the copies of one tile.  par = j & 1 fixes every LDS address of the tile: K halves 2j+1,
   //      2j+2 are read from ring slots 1, 2 (even j) or 3, 0 (odd j) while halves 2j+3, 2j+4 are
   //      copied into the other two; V(j) is read from V buffer par while V(j+1) is copied into
-  //      the other.
-  auto tile_copies = [&](int jt, const int par, bool in_main_loop) __attribute__((always_inline)) {
+  //      the other.  Table entries 4j+4 .. 4j+9 are involved: V(j+1) is entries +4..+7, K halves
+  //      2j+3, 2j+4 are +6..+9.  Every lane turns the id it holds into its page's address (two
+  //      vector instructions); the six addresses then move to scalar registers.
+  const uint64_t pool_k_u = (uint64_t)(size_t)pool_k;
+  const uint32_t page_stride_b = page_blocks << 12;
+  struct TilePages { const char* pb[6]; };
+  auto tile_pages = [&](int jt) __attribute__((always_inline)) {
+    const int32_t pg = min(max(ids_next, 0), a.num_pages - 1);   // checked by the plan; stay in bounds anyway
+    const uint64_t addr = pool_k_u + (uint64_t)(uint32_t)pg * page_stride_b;
+    const uint32_t lo = (uint32_t)addr, hi = (uint32_t)(addr >> 32);
+    TilePages tp;
+#pragma unroll
+    for (int i = 0; i < 6; ++i)
+      tp.pb[i] = (const char*)(size_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane(hi, i) << 32) |
+                                       (uint32_t)__builtin_amdgcn_readlane(lo, i));
+    ids_next = fetch_ids(4 * jt + 8);
+    return tp;
+  };
+  // copy c of the tile's eight: the pages of K half 2j+3, the first two of V(j+1), K half 2j+4,
+  // the last two of V(j+1) - the order in which the next tile needs them
+  auto tile_copy = [&](const TilePages& tp, const int par, int c) __attribute__((always_inline)) {
     const uint32_t k_h3 = lds_k + (par ? 1 : 3) * kHalfBytes;     // K half 2j+3 (copy target)
     const uint32_t k_h4 = lds_k + (par ? 2 : 0) * kHalfBytes;     // K half 2j+4 (copy target)
-    const uint32_t v_cur = lds_v + par * kTileBytes, v_nxt = lds_v + (par ^ 1) * kTileBytes;
+    const uint32_t v_nxt = lds_v + (par ^ 1) * kTileBytes;
+    switch (c) {
+      case 0: copy_page(tp.pb[2], false, k_h3); break;
+      case 1: copy_page(tp.pb[3], false, k_h3 + 4096); break;
+      case 2: copy_page(tp.pb[0], true, v_nxt); break;
+      case 3: copy_page(tp.pb[1], true, v_nxt + 4096); break;
+      case 4: copy_page(tp.pb[4], false, k_h4); break;
+      case 5: copy_page(tp.pb[5], false, k_h4 + 4096); break;
+      case 6: copy_page(tp.pb[2], true, v_nxt + 2 * 4096); break;
+      default: copy_page(tp.pb[3], true, v_nxt + 3 * 4096); break;
+    }
+  };
+  // last tile: zero the V rows of keys >= kv_len (their P is 0, their bytes are arbitrary)
+  auto zero_v_tail = [&](int jt, const int par) __attribute__((always_inline)) {
+    const uint32_t v_cur = lds_v + par * kTileBytes;
+    const int valid = kv_len - jt * kBN;
+    const u32x4 zero = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = i * 16 + (tid >> 4);
+      if (row >= valid)
+        *reinterpret_cast<u32x4 __attribute__((address_space(3)))*>(
+            (size_t)(v_cur + row * kRowBytes + (tid & 15) * 16)) = zero;
+    }
+    __syncthreads();
+  };
+  auto tile_copies = [&](int jt, const int par, bool in_main_loop) __attribute__((always_inline)) {
     if (in_main_loop || jt + 1 < n_kv_tiles) {
-      // table entries 4j+4 .. 4j+9: V(j+1) is entries +4..+7, K halves 2j+3, 2j+4 are +6..+9
-      const char* pb[6];
+      const TilePages tp = tile_pages(jt);
 #pragma unroll
-      for (int i = 0; i < 6; ++i) pb[i] = page_base(__builtin_amdgcn_readlane(ids_next, i));
-      ids_next = fetch_ids(4 * jt + 8);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) copy_page(pb[i], true, v_nxt + i * 4096);
-      copy_page(pb[2], false, k_h3);
-      copy_page(pb[3], false, k_h3 + 4096);
-      copy_page(pb[4], false, k_h4);
-      copy_page(pb[5], false, k_h4 + 4096);
+      for (int c = 0; c < 8; ++c) tile_copy(tp, par, c);
     } else if (kv_len < (jt + 1) * kBN) {
-      // last tile: zero the V rows of keys >= kv_len (their P is 0, their bytes are arbitrary)
-      const int valid = kv_len - jt * kBN;
-      const u32x4 zero = {0, 0, 0, 0};
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = i * 16 + (tid >> 4);
-        if (row >= valid)
-          *reinterpret_cast<u32x4 __attribute__((address_space(3)))*>(
-              (size_t)(v_cur + row * kRowBytes + (tid & 15) * 16)) = zero;
-      }
-      __syncthreads();
+      zero_v_tail(jt, par);
     }
   };
 
@@ -1080,10 +1112,22 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
       const uint32_t v_cur = lds_v + par * kTileBytes;
 #pragma unroll
       for (int f = 0; f < kAhead; ++f) kf[f] = k_frag(k_h1, f);
-      tile_copies(jt, par, in_main_loop);
-      half_step(fixed_ref, 2 * jt, k_h1, true, k_h2, v_cur, 0, s_a, s_b, mask0);
+      auto nothing = [](int) __attribute__((always_inline)) {};
+      if (in_main_loop) {
+        // the tile's copies go out one per MFMA slot of the first half step's second phase
+        // (addresses in the slot before), under the matrix pipe's work instead of ahead of it
+        TilePages tp;
+        half_step(fixed_ref, 2 * jt, k_h1, true, k_h2, v_cur, 0, s_a, s_b, mask0,
+                  [&](int slot) __attribute__((always_inline)) {
+                    if (slot == kCopySlot0 - 1) tp = tile_pages(jt);
+                    if (slot >= kCopySlot0 && slot < kCopySlot0 + 8) tile_copy(tp, par, slot - kCopySlot0);
+                  });
+      } else {
+        tile_copies(jt, par, false);
+        half_step(fixed_ref, 2 * jt, k_h1, true, k_h2, v_cur, 0, s_a, s_b, mask0, nothing);
+      }
       if (in_main_loop || 2 * jt + 1 < n_halves)
-        half_step(fixed_ref, 2 * jt + 1, k_h2, false, 0, v_cur, kHalf, s_b, s_a, mask1);
+        half_step(fixed_ref, 2 * jt + 1, k_h2, false, 0, v_cur, kHalf, s_b, s_a, mask1, nothing);
       wait_copies_and_sync();
     };
 
