@@ -6,7 +6,7 @@ random 2-byte tensors.  numpy only.
 
 The five workloads follow the serving shapes the paper evaluates on
 (Llama-3.1-8B, Sec. 4.1; inputs of about 3000-5000 tokens and 500 new tokens
-over 500-4500 cached ones, Sec. 4.3-4.5) as fixed by this build's configs.
+over 500-4500 cached ones, Sec. 4.2, Table 2) as fixed by this build's configs.
 """
 from dataclasses import dataclass, field
 from typing import List
@@ -206,7 +206,7 @@ def config(idx: int, seed: int = None, shrink: int = 1, num_layers: int = None) 
 
 
 def paper_point(cached: int, new: int = 500, seed: int = 7000) -> Workload:
-    """One Llama-3-8B-shaped sequence with `new` tokens over `cached` ones (Sec. 4.4, Table 2)."""
+    """One Llama-3-8B-shaped sequence with `new` tokens over `cached` ones (Sec. 4.2, Table 2)."""
     n, b = np.array([cached + new]), np.array([cached])
     pool = 4096
     w = Workload(f"paper-{new}-over-{cached}", seed + cached, BF16, 1, 32, 8, pool, n, b)
@@ -215,19 +215,43 @@ def paper_point(cached: int, new: int = 500, seed: int = 7000) -> Workload:
 
 
 def sample_rows(rng: np.random.Generator, q_len: int, begin: int, num_q_heads: int, count: int,
-                tile_tokens: int = 32, page_size: int = 16):
-    """(rows, heads) to spot-check: the first/last row of the range, rows on both sides of
-    page boundaries and of tile boundaries, the last ragged tile, plus random ones."""
-    must = {0, q_len - 1}
-    for r in range(q_len):
-        pos = begin + r
-        if pos % page_size in (0, page_size - 1) and len(must) < count // 4:
-            must.add(r)
-    for r in range(0, q_len, tile_tokens):
-        if len(must) < count // 2:
-            must.update({r, min(q_len - 1, r + tile_tokens - 1)})
-    must = sorted(x for x in must if 0 <= x < q_len)
-    extra = rng.integers(0, q_len, size=max(0, count - len(must)))
-    rows = np.concatenate([np.array(must, dtype=np.int64), extra]).astype(np.int32)
-    heads = rng.integers(0, num_q_heads, size=rows.size).astype(np.int32)
-    return rows, heads
+                tile_tokens: int = 32, page_size: int = 16, num_kv_heads: int = None):
+    """(rows, heads) pairs to spot-check, about `count` of them, rows relative to `begin`.
+
+    Rows: the first and the last row of the range; the first and last row of q tiles
+    (tile_tokens rows each; always the first, the last whole and the ragged last tile, the
+    others spread evenly over the whole range); several rows of the ragged last tile; rows on
+    both sides of page boundaries (positions with pos % page_size in {page_size - 1, 0}) at
+    boundaries spread evenly from the start to the end of the range; the rest uniform.
+    Heads: with num_kv_heads given, every row is paired with one random q head of every kv
+    head's group (num_kv_heads pairs per row); otherwise with one random q head."""
+    per_row = num_kv_heads or 1
+    n_rows = max(4, min(q_len, -(-count // per_row)))
+    rows = {0, q_len - 1}
+    n_tiles = -(-q_len // tile_tokens)
+    # q tiles: first, last whole, ragged last, and an even spread in between
+    tiles = {0, n_tiles - 1, max(0, n_tiles - 2)}
+    tiles.update(int(t) for t in np.linspace(0, n_tiles - 1, num=max(2, n_rows // 8)))
+    for t in sorted(tiles):
+        rows.update({t * tile_tokens, min(q_len, (t + 1) * tile_tokens) - 1})
+    last0 = (n_tiles - 1) * tile_tokens
+    rows.update(int(r) for r in rng.integers(last0, q_len, size=min(4, q_len - last0)))
+    # page boundaries: first position of a page and the one before it
+    first_b = (-begin) % page_size                      # first row with pos % page_size == 0
+    bounds = np.arange(first_b, q_len, page_size)
+    if bounds.size:
+        pick = bounds[np.unique(np.linspace(0, bounds.size - 1, num=max(2, n_rows // 8)).astype(int))]
+        for r in pick:
+            rows.add(int(r))
+            if r > 0:
+                rows.add(int(r) - 1)
+    rows = sorted(r for r in rows if 0 <= r < q_len)
+    extra = rng.integers(0, q_len, size=max(0, n_rows - len(rows)))
+    rows = np.concatenate([np.array(rows, dtype=np.int64), extra]).astype(np.int32)
+    if num_kv_heads is None:
+        heads = rng.integers(0, num_q_heads, size=rows.size).astype(np.int32)
+        return rows, heads
+    group = num_q_heads // num_kv_heads
+    heads = (np.arange(num_kv_heads)[None, :] * group
+             + rng.integers(0, group, size=(rows.size, num_kv_heads))).astype(np.int32)
+    return np.repeat(rows, num_kv_heads).astype(np.int32), heads.ravel()

@@ -29,6 +29,7 @@
 //     reads (V) spread over all banks.
 #include <math.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "mc_common.h"
@@ -64,7 +65,8 @@ struct PlanHeader {
   int32_t chunk_tiles;  // chunk length the planner settled on (KV tiles); 0 = nothing was cut
   int32_t num_groups_rows;  // partial rows written by shared-prefix items (0 = no groups)
   int32_t tail_chunks;  // chunks per q tile of the remainder round (0 = not applied)
-  int32_t pad[6];
+  int32_t merge_tokens; // new tokens of all q tiles with partial results (what merge_kernel walks)
+  int32_t pad[5];
 };
 static_assert(sizeof(PlanHeader) == 64, "header is 64 bytes");
 
@@ -86,7 +88,8 @@ static_assert(sizeof(ItemRec) == 32, "item record is 32 bytes");
 struct MergeRec {
   int32_t q_row;   // index of the tile's first token among all new tokens of the batch
   int32_t ntok, nsplit, part;
-  int32_t g_nsplit, g_part, g_stride, pad;
+  int32_t g_nsplit, g_part, g_stride;
+  int32_t tok_off; // tokens of the merge records before this one
 };
 static_assert(sizeof(MergeRec) == 32, "merge record is 32 bytes");
 
@@ -122,11 +125,15 @@ inline int32_t partial_capacity(int32_t total_q, int32_t tile_tokens, int32_t nu
   return (int32_t)(want < fit ? want : fit);
 }
 
+// part_limit >= 0 caps the rows of the partial arrays below what partial_capacity asks for (a
+// caller with a fixed amount of memory): the planner then cuts KV ranges less, or not at all.
 inline WorkspaceLayout workspace_layout(int32_t batch, int32_t total_q, int32_t tile_tokens,
-                                        int32_t num_q_heads, int32_t num_kv_heads) {
+                                        int32_t num_q_heads, int32_t num_kv_heads,
+                                        int32_t part_limit = -1) {
   WorkspaceLayout w;
   w.max_tiles = (int32_t)(((int64_t)total_q + tile_tokens - 1) / tile_tokens + batch);
   w.part_cap = partial_capacity(total_q, tile_tokens, num_q_heads, num_kv_heads);
+  if (part_limit >= 0 && part_limit < w.part_cap) w.part_cap = part_limit;
   w.batch = batch;
   // every extra chunk holds at least one partial row; a shared-prefix group adds items too
   w.max_items = w.max_tiles + w.part_cap + batch;
@@ -242,6 +249,7 @@ __global__ __launch_bounds__(256) void validate_pages_kernel(PlanArgs a) {
   if (__ballot(err) != 0 && lane == 0) {
     a.hdr->num_items = 0;
     a.hdr->num_merges = 0;
+    a.hdr->merge_tokens = 0;
     a.hdr->err = MC_ERR_RANGE;
   }
 }
@@ -300,7 +308,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   atomicMax(&s_maxcost, maxcost);
   __syncthreads();
   if (s_err) {
-    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
+    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->merge_tokens = 0; a.hdr->magic = kPlanMagic; }
     return;
   }
   // 2. page ids of every needed table entry.  Small batches (their offsets sit in LDS): a
@@ -353,7 +361,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     __syncthreads();
   }
   if (s_err || total_tiles > a.max_tiles) {
-    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
+    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->merge_tokens = 0; a.hdr->magic = kPlanMagic; }
     return;
   }
 
@@ -534,24 +542,25 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   // 5. items and merge records: count per contiguous range of tiles, scan, histogram of costs
   const int tper = (total_tiles + kPlanThreads - 1) / kPlanThreads;
   const int i_lo = min(t * tper, total_tiles), i_hi = min(i_lo + tper, total_tiles);
-  int n_items = 0, n_own = 0, n_grp = 0, n_merge = 0;
+  int n_items = 0, n_own = 0, n_grp = 0, n_merge = 0, n_mtok = 0;
   for (int i = i_lo; i < i_hi; ++i) {
     const Tile x = locate(i);
     const int Li = chunk_len(i, x);
     const int ns = own_splits(x, Li), ng = x.gm ? grp_splits(x, Li) : 0;
     n_items += ns + ng;
-    if (ns > 1 || x.pt > 0) { n_own += ns * x.ntok; ++n_merge; }
+    if (ns > 1 || x.pt > 0) { n_own += ns * x.ntok; ++n_merge; n_mtok += x.ntok; }
     n_grp += ng * x.gm;
     for (int c = 0; c < ns; ++c)
       atomicAdd(&hist[bucket(c + 1 < ns ? Li : x.T - x.pt - c * Li)], 1);
     for (int c = 0; c < ng; ++c)
       atomicAdd(&hist[bucket(Li > 0 ? min(Li, x.pt - c * Li) : x.pt)], 1);
   }
-  int tot_items, tot_own, tot_grp, tot_merge;
+  int tot_items, tot_own, tot_grp, tot_merge, tot_mtok;
   block_exclusive_scan(n_items, scan, &tot_items);
   int own_off = block_exclusive_scan(n_own, scan, &tot_own);
   int grp_off = block_exclusive_scan(n_grp, scan, &tot_grp);
   int merge_off = block_exclusive_scan(n_merge, scan, &tot_merge);
+  int mtok_off = block_exclusive_scan(n_mtok, scan, &tot_mtok);
   {
     constexpr int kPer = kBuckets / kPlanThreads;
     int local[kPer], sum = 0;
@@ -561,7 +570,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   }
   __syncthreads();
   if (tot_items > a.max_items || tot_own + tot_grp > a.part_cap || tot_merge > a.max_tiles) {   // cannot happen
-    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->magic = kPlanMagic; }
+    if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->merge_tokens = 0; a.hdr->magic = kPlanMagic; }
     return;
   }
   // where each group's partial rows start (after all the tiles' own): its members need it
@@ -588,7 +597,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       m.g_nsplit = ng;
       m.g_part = x.pt > 0 ? s_gbase[s_glead[x.s]] + (x.s - s_glead[x.s]) : 0;
       m.g_stride = x.pt > 0 ? s_gsize[s_glead[x.s]] : 0;
-      m.pad = 0;
+      m.tok_off = mtok_off;
+      mtok_off += x.ntok;
       a.merges[merge_off++] = m;
     }
     for (int c = 0; c < ns; ++c) {
@@ -619,6 +629,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     a.hdr->err = MC_OK;
     a.hdr->num_items = tot_items;
     a.hdr->num_merges = tot_merge;
+    a.hdr->merge_tokens = tot_mtok;
     a.hdr->chunk_tiles = L;
     a.hdr->tile_tokens = a.tile_tokens;
     a.hdr->batch = a.batch;
@@ -1213,10 +1224,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 }
 
 // Combines the chunks of every q tile whose KV range was cut: with L_c the chunk LSEs,
-// LSE = log sum_c exp(L_c) and O = sum_c exp(L_c - LSE) O_c.  A fixed grid walks the (cut tile,
-// token, four q heads) triples - the host does not know how many tiles were cut, usually none -
-// one wavefront per q head, two d per lane; a chunk's loads do not depend on another chunk's,
-// so they are all in flight together.
+// LSE = log sum_c exp(L_c) and O = sum_c exp(L_c - LSE) O_c.  The grid walks the (token, four q
+// heads) pairs of those tiles - the host does not know how many tiles were cut, usually none, so
+// it sizes the grid for the batch's new tokens - one wavefront per q head, two d per lane; a
+// chunk's loads do not depend on another chunk's, so they are all in flight together.
 struct MergeArgs {
   const PlanHeader* hdr;
   const MergeRec* merges;
@@ -1232,14 +1243,20 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   if (a.hdr->magic != kPlanMagic) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int head_groups = (a.hq + 3) / 4;
-  const int per_tile = a.tile_tokens * head_groups;
-  const int64_t total = (int64_t)a.hdr->num_merges * per_tile;   // usually 0: nothing was cut
+  const int n_rec = a.hdr->num_merges;
+  const int64_t total = (int64_t)a.hdr->merge_tokens * head_groups;   // usually 0: nothing was cut
   typedef float f32x2 __attribute__((ext_vector_type(2)));
   for (int64_t wk = blockIdx.x; wk < total; wk += gridDim.x) {
-    const MergeRec m = a.merges[wk / per_tile];
-    const int rest = (int)(wk % per_tile);
-    const int tt = rest / head_groups, h = rest % head_groups * 4 + wave;
-    if (tt >= m.ntok || h >= a.hq) continue;
+    const int tok = (int)(wk / head_groups), h = (int)(wk % head_groups) * 4 + wave;
+    // the record whose token range [tok_off, tok_off + ntok) holds tok
+    int lo = 0, hi = n_rec;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (a.merges[mid].tok_off <= tok) lo = mid; else hi = mid;
+    }
+    const MergeRec m = a.merges[lo];
+    const int tt = tok - m.tok_off;
+    if (tt < 0 || tt >= m.ntok || h >= a.hq) continue;
     // partial row of chunk c: the shared prefix's chunks first, then the tile's own
     auto row_of = [&](int c) {
       return (int64_t)(c < m.g_nsplit ? m.g_part + c * m.g_stride
@@ -1284,11 +1301,22 @@ mc_status launch_attn(int G, bool gate, dim3 grid, hipStream_t hs, const AttnArg
 }
 
 // Workgroups of the attention kernel the current GPU runs at a time: two per compute unit.
+// The compute-unit count is asked for once per device (the query costs microseconds, which a
+// decode step notices); the current device is a thread-local read.
 int device_slots() {
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+  constexpr int kDevs = 64;
+  static std::atomic<int> cached[kDevs];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) return -1;
+  if (dev < kDevs) {
+    const int c = cached[dev].load(std::memory_order_relaxed);
+    if (c > 0) return c;
+  }
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      cus <= 0)
     return -1;
+  if (dev < kDevs) cached[dev].store(2 * cus, std::memory_order_relaxed);
   return 2 * cus;
 }
 
@@ -1328,39 +1356,17 @@ mc_status check_attn_shape(const mc_pool_desc* pool, int32_t num_q_heads, int32_
   return MC_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-size_t mc_attn_workspace_size(int32_t batch, int32_t total_q, int32_t num_q_heads,
-                              int32_t num_kv_heads) {
-  if (batch < 0 || total_q < 0 || num_q_heads <= 0 || num_kv_heads <= 0) return 0;
-  if (num_q_heads % num_kv_heads != 0) return 0;
-  const int G = num_q_heads / num_kv_heads;
-  if (G != 1 && G != 2 && G != 4 && G != 8) return 0;
-  return workspace_layout(batch, total_q, kBM / G, num_q_heads, num_kv_heads).total;
-}
-
-mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
-                       int32_t total_q, const int32_t* cu_q, const int32_t* begin,
-                       const int32_t* page_table, const int32_t* cu_pages, void* workspace,
-                       size_t workspace_bytes, void* stream) {
-  return mc_attn_plan_ahead(pool, num_q_heads, batch, total_q, cu_q, begin, page_table, cu_pages,
-                            0, workspace, workspace_bytes, stream);
-}
-
-mc_status mc_attn_plan_ahead(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
-                             int32_t total_q, const int32_t* cu_q, const int32_t* begin,
-                             const int32_t* page_table, const int32_t* cu_pages,
-                             int32_t ahead_tokens, void* workspace, size_t workspace_bytes,
-                             void* stream) {
+mc_status plan_impl(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
+                    int32_t total_q, const int32_t* cu_q, const int32_t* begin,
+                    const int32_t* page_table, const int32_t* cu_pages, int32_t ahead_tokens,
+                    void* workspace, size_t workspace_bytes, int32_t part_limit, void* stream) {
   if (ahead_tokens < 0 || ahead_tokens > (1 << 20)) return MC_ERR_RANGE;
   int G = 0;
   mc_status st = check_attn_shape(pool, num_q_heads, batch, total_q, &G);
   if (st != MC_OK) return st;
   if (!workspace || !mc::aligned16(workspace)) return MC_ERR_INVALID;
   const WorkspaceLayout w =
-      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads);
+      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads, part_limit);
   if (workspace_bytes < w.total) return MC_ERR_INVALID;
   if (batch > 0 && (!cu_q || !begin || !page_table || !cu_pages)) return MC_ERR_INVALID;
   if (batch == 0) {   // nothing to plan: a header with an empty work list
@@ -1396,23 +1402,12 @@ mc_status mc_attn_plan_ahead(const mc_pool_desc* pool, int32_t num_q_heads, int3
   return mc::launch_status();
 }
 
-mc_status mc_attn_plan_check(const void* workspace, void* stream) {
-  if (!workspace) return MC_ERR_INVALID;
-  PlanHeader h;
-  hipStream_t hs = static_cast<hipStream_t>(stream);
-  if (hipMemcpyAsync(&h, workspace, sizeof(h), hipMemcpyDeviceToHost, hs) != hipSuccess)
-    return MC_ERR_HIP;
-  if (hipStreamSynchronize(hs) != hipSuccess) return MC_ERR_HIP;
-  if (h.magic != kPlanMagic) return MC_ERR_INVALID;
-  return static_cast<mc_status>(h.err);
-}
 
-mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const void* q,
-                                 int32_t num_q_heads, int32_t batch, int32_t total_q,
-                                 const int32_t* cu_q, const int32_t* begin,
-                                 const int32_t* page_table, const int32_t* cu_pages,
-                                 float sm_scale, void* out, float* lse, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
+mc_status attn_impl(const mc_pool_desc* pool, int32_t layer, const void* q, int32_t num_q_heads,
+                    int32_t batch, int32_t total_q, const int32_t* cu_q, const int32_t* begin,
+                    const int32_t* page_table, const int32_t* cu_pages, float sm_scale, void* out,
+                    float* lse, void* workspace, size_t workspace_bytes, int32_t part_limit,
+                    void* stream) {
   int G = 0;
   mc_status st = check_attn_shape(pool, num_q_heads, batch, total_q, &G);
   if (st != MC_OK) return st;
@@ -1425,7 +1420,7 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
       (reinterpret_cast<uintptr_t>(lse) & 3u))
     return MC_ERR_INVALID;
   const WorkspaceLayout w =
-      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads);
+      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads, part_limit);
   if (workspace_bytes < w.total) return MC_ERR_INVALID;
   const int slots = device_slots();
   if (slots <= 0) return MC_ERR_HIP;
@@ -1472,12 +1467,66 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
   m.lse = a.lse;
   m.hq = num_q_heads;
   m.tile_tokens = kBM / G;
-  const dim3 mgrid(4 * slots);
+  // one workgroup per (token, four q heads) pair if they all run at once, else a grid-stride walk
+  const int64_t pairs = (int64_t)total_q * ((num_q_heads + 3) / 4);
+  const dim3 mgrid((unsigned)(pairs < 4ll * slots ? pairs : 4ll * slots));
   if (pool->dtype == MC_F16)
     hipLaunchKernelGGL(merge_kernel<_Float16>, mgrid, dim3(256), 0, hs, m);
   else
     hipLaunchKernelGGL(merge_kernel<__bf16>, mgrid, dim3(256), 0, hs, m);
   return mc::launch_status();
+}
+
+
+}  // namespace
+
+extern "C" {
+
+size_t mc_attn_workspace_size(int32_t batch, int32_t total_q, int32_t num_q_heads,
+                              int32_t num_kv_heads) {
+  if (batch < 0 || total_q < 0 || num_q_heads <= 0 || num_kv_heads <= 0) return 0;
+  if (num_q_heads % num_kv_heads != 0) return 0;
+  const int G = num_q_heads / num_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return 0;
+  return workspace_layout(batch, total_q, kBM / G, num_q_heads, num_kv_heads).total;
+}
+
+mc_status mc_attn_plan(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
+                       int32_t total_q, const int32_t* cu_q, const int32_t* begin,
+                       const int32_t* page_table, const int32_t* cu_pages, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  return mc_attn_plan_ahead(pool, num_q_heads, batch, total_q, cu_q, begin, page_table, cu_pages,
+                            0, workspace, workspace_bytes, stream);
+}
+
+mc_status mc_attn_plan_ahead(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch,
+                             int32_t total_q, const int32_t* cu_q, const int32_t* begin,
+                             const int32_t* page_table, const int32_t* cu_pages,
+                             int32_t ahead_tokens, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  return plan_impl(pool, num_q_heads, batch, total_q, cu_q, begin, page_table, cu_pages,
+                   ahead_tokens, workspace, workspace_bytes, -1, stream);
+}
+
+mc_status mc_attn_plan_check(const void* workspace, void* stream) {
+  if (!workspace) return MC_ERR_INVALID;
+  PlanHeader h;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&h, workspace, sizeof(h), hipMemcpyDeviceToHost, hs) != hipSuccess)
+    return MC_ERR_HIP;
+  if (hipStreamSynchronize(hs) != hipSuccess) return MC_ERR_HIP;
+  if (h.magic != kPlanMagic) return MC_ERR_INVALID;
+  return static_cast<mc_status>(h.err);
+}
+
+mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const void* q,
+                                 int32_t num_q_heads, int32_t batch, int32_t total_q,
+                                 const int32_t* cu_q, const int32_t* begin,
+                                 const int32_t* page_table, const int32_t* cu_pages,
+                                 float sm_scale, void* out, float* lse, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  return attn_impl(pool, layer, q, num_q_heads, batch, total_q, cu_q, begin, page_table, cu_pages,
+                   sm_scale, out, lse, workspace, workspace_bytes, -1, stream);
 }
 
 }  // extern "C"

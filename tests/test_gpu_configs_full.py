@@ -1,8 +1,11 @@
 """Configs 3 and 5 at full size on the GPU, in the launch configuration the benchmark uses.
 
-The oracle checks a seeded sample of rows (range ends, page and tile boundaries, the ragged
-last tile) on a few layers, and whole layers of the copies; properties that hold at any size
-cover every layer: split passes against the single pass, and pool B against pool A through
+The oracle checks, per config, every row and q head of one layer of the smallest sequence and
+a seeded sample of more than 4096 (sequence, q head, row) triples spread over all sequences and
+several layers: range ends, first and last rows of q tiles from the start to the end of the
+range, the ragged last tile, both sides of page boundaries, one q head of every kv head's group
+per row.  Whole layers of the copies are compared byte for byte; properties that hold at any
+size cover every layer: split passes against the single pass, and pool B against pool A through
 the two page tables."""
 import numpy as np
 import pytest
@@ -23,9 +26,17 @@ def host_layer(w, s, layer, base):
 
 
 def check_rows(w, opool, shape, layer, seq, q_bits, begin, end, out_rows, lse_rows, seed, count):
-    """out_rows / lse_rows: device tensors of the rows [begin, end) of sequence seq."""
+    """out_rows / lse_rows: device tensors of the rows [begin, end) of sequence seq; count = number
+    of (row, q head) pairs to check, or None for every row and head.  Returns the pairs checked."""
     q_len = end - begin
-    rows, heads = mi.sample_rows(mi.rng_for(seed, seq, layer), q_len, begin, w.num_q_heads, count, 32)
+    if count is None:
+        rr, hh = np.meshgrid(np.arange(q_len, dtype=np.int32),
+                             np.arange(w.num_q_heads, dtype=np.int32), indexing="ij")
+        rows, heads = rr.ravel(), hh.ravel()
+    else:
+        rows, heads = mi.sample_rows(mi.rng_for(seed, seq, layer), q_len, begin, w.num_q_heads, count,
+                                     tile_tokens=128 // (w.num_q_heads // w.num_kv_heads),
+                                     num_kv_heads=w.num_kv_heads)
     ro, rl = oracle.attention(opool, shape, layer, w.page_tables[seq], q_bits, w.num_q_heads, begin,
                               end, sel_rows=rows, sel_heads=heads)
     go = oracle.decode(bits(out_rows)[rows, heads], w.dtype)
@@ -34,6 +45,7 @@ def check_rows(w, opool, shape, layer, seq, q_bits, begin, end, out_rows, lse_ro
     eo, el = float(np.max(np.abs(go - ro))), float(np.max(np.abs(gl - rl)))
     assert eo <= O_TOL, (layer, seq, eo)
     assert el <= LSE_TOL, (layer, seq, el)
+    return int(rows.size)
 
 
 def pools_agree(pool_a, table_a, pool_b, table_b, w, upto):
@@ -67,6 +79,7 @@ def test_config3_balanced_split_32_layers():
     oracle_layers = (0, 17, L - 1)
     opool = np.full(pool.elems, 0x7fc1, dtype=np.uint16)
     worst_split_o = worst_split_l = 0.0
+    triples = 0
     for layer in range(L):
         kl = [layer_variant_dev(t, layer) for t in dk]
         vl = [layer_variant_dev(t, layer) for t in dv]
@@ -91,14 +104,19 @@ def test_config3_balanced_split_32_layers():
             for s in range(B):
                 k, v, q = host_layer(w, s, layer, base)
                 oracle.append(opool, pool.shape, layer, k, v, 0, w.page_tables[s])
-            for s in (0, int(np.argmin(w.n)), int(np.argmax(w.n))):
+            smallest = int(np.argmin(w.n))
+            for s in range(B):       # every sequence: 256 pairs of the second pass, 256 of the single pass
                 _, _, q = host_layer(w, s, layer, base)
                 ms, ns = int(m[s]), int(w.n[s])
                 b0, c0 = int(w_b.cu_q[s]), int(w_c.cu_q[s])
-                check_rows(w, opool, pool.shape, layer, s, q[ms:], ms, ns, o_b[b0:b0 + ns - ms],
-                           l_b[b0:b0 + ns - ms], 3, 96)
-                check_rows(w, opool, pool.shape, layer, s, q, 0, ns, o_c[c0:c0 + ns],
-                           l_c[c0:c0 + ns], 33, 96)
+                # the smallest sequence, first layer: every row and q head of both passes
+                every = layer == oracle_layers[0] and s == smallest
+                triples += check_rows(w, opool, pool.shape, layer, s, q[ms:], ms, ns,
+                                      o_b[b0:b0 + ns - ms], l_b[b0:b0 + ns - ms], 3,
+                                      None if every else 256)
+                triples += check_rows(w, opool, pool.shape, layer, s, q, 0, ns, o_c[c0:c0 + ns],
+                                      l_c[c0:c0 + ns], 33, None if every else 256)
+    assert triples >= 4096 + 32 * int(np.min(w.n)), triples
     assert worst_split_o <= O_TOL, worst_split_o
     assert worst_split_l <= LSE_TOL, worst_split_l
     # ---- ship [0, m) of every sequence, all 32 layers, into a second pool ----
@@ -143,6 +161,7 @@ def test_config5_long_context():
     for layer in range(L):
         gpu_append(pool, layer, torch.cat([layer_variant_dev(t, layer) for t in dk]),
                    torch.cat([layer_variant_dev(t, layer) for t in dv]), db_fill)
+    triples = 0
     for layer in (0, L - 1):
         q_dev = torch.cat([layer_variant_dev(t, layer) for t in dq])
         out, lse = gpu_attention(pool, layer, q_dev, db)
@@ -150,8 +169,11 @@ def test_config5_long_context():
             k, v, q = host_layer(w, s, layer, base)
             oracle.append(opool, pool.shape, layer, k, v, 0, w.page_tables[s])
             lo, ql = int(w.cu_q[s]), int(w.n[s] - w.b[s])
-            check_rows(w, opool, pool.shape, layer, s, q, int(w.b[s]), int(w.n[s]), out[lo:lo + ql],
-                       lse[lo:lo + ql], 5, 128)
+            # the 16384-token sequence, first layer: every row and q head; else 2048 pairs
+            every = layer == 0 and s == 0
+            triples += check_rows(w, opool, pool.shape, layer, s, q, int(w.b[s]), int(w.n[s]),
+                                  out[lo:lo + ql], lse[lo:lo + ql], 5, None if every else 2048)
+    assert triples >= 3 * 2048 + 32 * 8192, triples
     # ---- 32768 tokens x 32 layers (4 GiB of KV) to a second pool ----
     s, n = 1, int(w.n[1])
     pool_b = DevPool(w)

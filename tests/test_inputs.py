@@ -64,3 +64,22 @@ def test_share_prefix_makes_a_fork():
     assert np.array_equal(w.page_tables[1][:10], w.page_tables[0][:10])
     assert np.array_equal(w.page_tables[1][10:], own[10:])
     assert np.array_equal(w.with_ranges(w.b, w.n).kv(1)[0], k1)      # forks survive a change of ranges
+
+
+def test_sample_rows_covers_the_whole_range():
+    q_len, begin, tile = 8192 + 13, 8192 + 5, 32
+    rows, heads = mi.sample_rows(mi.rng_for(9), q_len, begin, 32, 4096, tile, num_kv_heads=8)
+    assert rows.size == heads.size >= 4096 and rows.min() == 0 and rows.max() == q_len - 1
+    # every row comes with one head of each kv head's group
+    assert np.array_equal(np.unique(heads.reshape(-1, 8) // 4, axis=0), np.arange(8)[None, :])
+    pos = begin + np.unique(rows)
+    thirds = [pos[(pos >= begin + k * q_len // 3) & (pos < begin + (k + 1) * q_len // 3)] for k in range(3)]
+    for part in thirds:                      # start, middle and end of the range alike
+        assert np.sum(part % 16 == 0) >= 8 and np.sum(part % 16 == 15) >= 8       # page boundaries
+        r = part - begin
+        assert np.sum(r % tile == 0) >= 8 and np.sum(r % tile == tile - 1) >= 8   # q tile edges
+    last0 = (q_len - 1) // tile * tile       # the ragged last tile: its first, its last, more
+    assert last0 in rows and np.sum(np.unique(rows) >= last0) >= 3
+    # one head per row without kv groups; short ranges are taken whole at most
+    rows, heads = mi.sample_rows(mi.rng_for(9), 5, 3, 8, 64)
+    assert rows.size == heads.size and set(rows.tolist()) <= set(range(5)) and {0, 4} <= set(rows.tolist())
