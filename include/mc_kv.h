@@ -219,6 +219,30 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer,
                                  float* lse /* device [total_q][Hq] */,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory and so cannot bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  mc_attn_plan followed by mc_prefix_prefill_attn with the same
+ * arguments and results, the workspace being an 8 MiB array inside the library
+ * (one copy per GPU the library has run on, held until the process ends).  The
+ * call allocates nothing and does not synchronise.
+ *   - Limit: the work list of the batch must fit the array - MC_ERR_RANGE, nothing
+ *     launched, for batches beyond about 100000 q tiles; the room left over holds
+ *     partial results, so KV ranges are cut into fewer chunks than with a full
+ *     workspace (the results agree within the rounding of the merge).
+ *   - There is no blocking check: malformed offsets, short tables or page ids
+ *     outside the pool leave out and lse unwritten, as after a failed plan.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time
+ *     on one GPU (different streams, different host threads) race.  Calls on one
+ *     stream, one after the other, are fine; nothing needs clearing in between. */
+mc_status mc_prefix_prefill_attn_noalloc(const mc_pool_desc* pool, int32_t layer,
+                                         const void* q /* device [total_q][Hq][D] */,
+                                         int32_t num_q_heads, int32_t batch, int32_t total_q,
+                                         const int32_t* cu_q, const int32_t* begin,
+                                         const int32_t* page_table, const int32_t* cu_pages,
+                                         float sm_scale /* 0 -> 1/sqrt(D) */,
+                                         void* out /* device [total_q][Hq][D], pool dtype */,
+                                         float* lse /* device [total_q][Hq] */, void* stream);
+
 /* ---- transfer payload: pages <-> contiguous buffer -------------------------
  * (sender and receiver side of remote_send: KV of prompt[begin:end] goes to the
  * page/slot entries reserved by prep_recv, Sec. 3.1, Sec. 3.2 Example 2; a

@@ -17,7 +17,7 @@ EXPORTS = [
     "mc_kv_allocator_create", "mc_kv_allocator_destroy", "mc_kv_alloc_pages", "mc_kv_free_pages",
     "mc_kv_allocator_num_free", "mc_kv_check_page_table",
     "mc_kv_append", "mc_kv_append_send", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_ahead", "mc_attn_plan_check",
-    "mc_prefix_prefill_attn", "mc_kv_pack_range", "mc_kv_unpack_range",
+    "mc_prefix_prefill_attn", "mc_prefix_prefill_attn_noalloc", "mc_kv_pack_range", "mc_kv_unpack_range",
     "mc_kv_pack_batch", "mc_kv_unpack_batch",
     "mc_mfma_probe_operand_bytes", "mc_mfma_probe",
     "mc_plan_remote_send", "mc_addr_compress", "mc_addr_expand",
@@ -76,6 +76,8 @@ def lib():
     L.mc_attn_plan_check.argtypes = [vp, vp]
     L.mc_prefix_prefill_attn.argtypes = [pd, i32, vp, i32, i32, i32, vp, vp, vp, vp, C.c_float,
                                          vp, vp, vp, sz, vp]
+    L.mc_prefix_prefill_attn_noalloc.argtypes = [pd, i32, vp, i32, i32, i32, vp, vp, vp, vp,
+                                                 C.c_float, vp, vp, vp]
     L.mc_kv_pack_range.argtypes = [pd, i32, i32, vp, i32, i32, i32, vp, vp]
     L.mc_kv_unpack_range.argtypes = [pd, i32, i32, vp, i32, i32, i32, vp, vp]
     L.mc_kv_pack_batch.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
@@ -221,6 +223,15 @@ def mc_prefix_prefill_attn(pool: mc_pool_desc, layer, q, num_q_heads, batch, tot
                                         float(sm_scale), _ptr(out), _ptr(lse), _ptr(workspace),
                                         workspace_bytes, _stream(stream)),
            "mc_prefix_prefill_attn")
+
+
+def mc_prefix_prefill_attn_noalloc(pool: mc_pool_desc, layer, q, num_q_heads, batch, total_q, cu_q,
+                                   begin, page_table, cu_pages, sm_scale, out, lse, stream=None):
+    _check(lib().mc_prefix_prefill_attn_noalloc(C.byref(pool), layer, _ptr(q), num_q_heads, batch,
+                                                total_q, _ptr(cu_q), _ptr(begin),
+                                                _ptr(page_table), _ptr(cu_pages), float(sm_scale),
+                                                _ptr(out), _ptr(lse), _stream(stream)),
+           "mc_prefix_prefill_attn_noalloc")
 
 
 def mc_kv_pack_range(pool: mc_pool_desc, layer_begin, layer_end, pages, n_table_pages, s0, s1,

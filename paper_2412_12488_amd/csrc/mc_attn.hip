@@ -30,6 +30,7 @@
 #include <math.h>
 
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "mc_common.h"
@@ -1478,6 +1479,31 @@ mc_status attn_impl(const mc_pool_desc* pool, int32_t layer, const void* q, int3
 }
 
 
+// ---- scratch of the entry point that allocates nothing ---------------------------------
+// The attention workspace (work list, partial rows) of mc_prefix_prefill_attn_noalloc lives in
+// this array; every GPU the library runs on holds its own copy until the process ends.
+constexpr size_t kScratchBytes = size_t(8) << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// Device address of the current device's copy of `scratch` (in host code the array's name is
+// only a handle for this look-up, never an address a kernel may use).  Looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+mc_status scratch_of_current_device(void** ptr_out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MC_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *ptr_out = g_scratch_ptr[dev];
+  return MC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1527,6 +1553,35 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer, const 
                                  size_t workspace_bytes, void* stream) {
   return attn_impl(pool, layer, q, num_q_heads, batch, total_q, cu_q, begin, page_table, cu_pages,
                    sm_scale, out, lse, workspace, workspace_bytes, -1, stream);
+}
+
+mc_status mc_prefix_prefill_attn_noalloc(const mc_pool_desc* pool, int32_t layer, const void* q,
+                                         int32_t num_q_heads, int32_t batch, int32_t total_q,
+                                         const int32_t* cu_q, const int32_t* begin,
+                                         const int32_t* page_table, const int32_t* cu_pages,
+                                         float sm_scale, void* out, float* lse, void* stream) {
+  int G = 0;
+  mc_status st = check_attn_shape(pool, num_q_heads, batch, total_q, &G);
+  if (st != MC_OK) return st;
+  // the work list alone must fit; what is left holds partial rows (32-byte item record, LSE
+  // and O per row and q head), fewer than the caller-workspace variant may ask for
+  const WorkspaceLayout fixed =
+      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads, 0);
+  if (fixed.total + 4096 > kScratchBytes) return MC_ERR_RANGE;
+  const size_t per_row = sizeof(ItemRec) + sizeof(float) * (size_t)num_q_heads * (mc::kHeadDim + 1);
+  int32_t part_limit = (int32_t)((kScratchBytes - fixed.total - 4096) / per_row);
+  while (part_limit > 0 &&
+         workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads, part_limit)
+                 .total > kScratchBytes)
+    --part_limit;
+  void* ws = nullptr;
+  st = scratch_of_current_device(&ws);
+  if (st != MC_OK) return st;
+  st = plan_impl(pool, num_q_heads, batch, total_q, cu_q, begin, page_table, cu_pages, 0, ws,
+                 kScratchBytes, part_limit, stream);
+  if (st != MC_OK) return st;
+  return attn_impl(pool, layer, q, num_q_heads, batch, total_q, cu_q, begin, page_table, cu_pages,
+                   sm_scale, out, lse, ws, kScratchBytes, part_limit, stream);
 }
 
 }  // extern "C"
