@@ -80,10 +80,67 @@ def attention_workload(name):
     raise SystemExit(f"unknown workload {name}; choose from {ATTN_WORKLOADS}")
 
 
-def attention_only(name, iters, values="normal"):
-    """Attention kernel alone on resident Q/K/V: one JSON line.  For rocprofv3 runs.
-    values: "normal" = N(0,1) like the workload; "zero" = all zeros (same instructions, the
-    least operand switching: shows how far the data's power draw holds the clock down)."""
+def launch_stats(fn, iters, warm=2):
+    """Per-call milliseconds of fn (HIP events between consecutive calls on the current
+    stream): mean, median and minimum over iters calls after warm untimed ones."""
+    import numpy as np
+    import torch
+    for _ in range(warm):
+        fn()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+    ev[0].record()
+    for i in range(iters):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    t = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(iters)])
+    return {"mean": float(t.mean()), "median": float(np.median(t)), "min": float(t.min())}
+
+
+def oracle_sample_check(w, pool_bits, q_bits, out_t, lse_t, triples, seed=17):
+    """A bounded sample of (sequence, row, q head) triples of an attention result against the
+    CPU oracle (fp64), with the oracle's time for the sample (mostly the gather of each
+    sequence's K/V through its page table).  pool_bits / q_bits: host uint16 arrays of what the
+    GPU read."""
+    import time
+
+    import numpy as np
+
+    import mc_inputs as mi
+    import oracle
+    shape = oracle.Shape(1, w.num_pages, 16, w.num_kv_heads, 128, w.dtype)
+    out_b = out_t.cpu().numpy().view(np.uint16)
+    lse_h = lse_t.cpu().numpy().astype(np.float64)
+    G = w.num_q_heads // w.num_kv_heads
+    live = [s for s in range(w.batch) if w.n[s] > w.b[s]]
+    err_o = err_l = 0.0
+    t_or, fl_sample, n_done = 0.0, 0, 0
+    for s in live:
+        q_len, b, lo = int(w.n[s] - w.b[s]), int(w.b[s]), int(w.cu_q[s])
+        rows, heads = mi.sample_rows(mi.rng_for(seed, s), q_len, b, w.num_q_heads,
+                                     max(w.num_kv_heads, triples // len(live)),
+                                     tile_tokens=128 // G, num_kv_heads=w.num_kv_heads)
+        qs = q_bits[lo:lo + q_len]
+        c0 = time.perf_counter()
+        ro, rl = oracle.attention(pool_bits, shape, 0, w.page_tables[s], qs, w.num_q_heads, b,
+                                  int(w.n[s]), sel_rows=rows, sel_heads=heads)
+        t_or += time.perf_counter() - c0
+        go = oracle.decode(out_b[lo:lo + q_len][rows, heads], w.dtype)
+        err_o = max(err_o, float(np.max(np.abs(go - ro))))
+        err_l = max(err_l, float(np.max(np.abs(lse_h[lo:lo + q_len][rows, heads] - rl))))
+        fl_sample += int(np.sum(4 * 128 * (b + rows.astype(np.int64) + 1)))
+        n_done += int(rows.size)
+    return {"triples": n_done, "max_abs_err_O": round(err_o, 6), "max_abs_err_LSE": round(err_l, 8),
+            "oracle_s": round(t_or, 2), "oracle_cores": len(os.sched_getaffinity(0)),
+            "sample_flops": fl_sample}
+
+
+def attention_only(name, iters, values="normal", oracle_triples=0, mfma_ceiling=None):
+    """Attention kernel alone on resident Q/K/V: one dict.  For rocprofv3 runs and the
+    per-workload table.  values: "normal" = N(0,1) like the workload; "zero" = all zeros (same
+    instructions, the least operand switching: shows how far the data's power draw holds the
+    clock down).  oracle_triples > 0: that many sampled outputs are checked against the CPU
+    oracle after the timing.  mfma_ceiling: measured MFMA-alone rate (TFLOP/s) to relate to."""
     import numpy as np
     import torch
 
@@ -107,24 +164,116 @@ def attention_only(name, iters, values="normal"):
     mc.mc_attn_plan_check(ws)
     run = lambda: mc.mc_prefix_prefill_attn(desc, 0, q, Hq, w.batch, tq, cu_q, begin, table, cu_pages,
                                             0.0, out, lse, ws, wsb)
-    for _ in range(2):
-        run()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(iters):
-        run()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / iters
+    st = launch_stats(run, iters)
+    ms = st["mean"]
     fl = w.useful_flops()
     alg_bytes = 2 * tq * Hq * 256 + tq * Hq * 4 + int(np.sum(w.n)) * w.token_bytes
     res = {"workload": w.name, "values": values, "new_tokens": tq,
            "kv_tokens": int(np.sum(w.n)),
            "algorithmic_GBps": round(alg_bytes / ms / 1e6, 1),
-           "useful_flops": fl, "ms": round(ms, 4),
+           "useful_flops": fl, "ms": round(ms, 4), "ms_median": round(st["median"], 4),
+           "ms_min": round(st["min"], 4),
            "TFLOPs": round(fl / ms / 1e9, 1),
            "frac_of_mfma_peak": round(fl / ms / 1e9 / MFMA_PEAK_TFLOPS, 4)}
+    if mfma_ceiling:
+        res["frac_of_measured_mfma_rate"] = round(fl / ms / 1e9 / mfma_ceiling, 4)
+    if oracle_triples:
+        res["oracle_sample"] = oracle_sample_check(
+            w, pool.view(torch.int16).cpu().numpy().view(np.uint16),
+            q.view(torch.int16).cpu().numpy().view(np.uint16).reshape(tq, Hq, 128), out, lse,
+            oracle_triples)
     del pool, q, out, lse, ws
+    torch.cuda.empty_cache()
+    return res
+
+
+def layer_overlap(w, layers, iters=5):
+    """`layers` layers of the workload, append + attention per layer on the main stream, each
+    layer's KV shipped to a second pool (pack + unpack) either on the same stream after the
+    layer's attention, or on a side stream beside the next layer's work (paper Sec. 3.6: a
+    computation stream and a communication stream).  Both streams have the default priority.
+    Returns milliseconds for the whole pass and per attention launch, both ways."""
+    import numpy as np
+    import torch
+
+    import mc_inputs as mi
+    import paper_2412_12488_amd as mc
+    dev = "cuda:0"
+    B, Hq, Hkv = w.batch, w.num_q_heads, w.num_kv_heads
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    tq, n_tok = int(w.cu_q[-1]), int(np.sum(w.n))
+    # pages of the whole batch, scattered in a pool of 8 x that many pages per layer
+    pages = 8 * int(sum(-(-int(t) // 16) for t in w.n))
+    tab_a = mi.scatter_page_tables(mi.rng_for(w.seed, 301), pages, w.n)
+    tab_b = mi.scatter_page_tables(mi.rng_for(w.seed, 302), pages, w.n)
+    elems = layers * pages * 2 * Hkv * 16 * 128
+    pool_a = torch.randn(elems, dtype=torch.bfloat16, device=dev)
+    pool_b = torch.empty(elems, dtype=torch.bfloat16, device=dev)
+    da = mc.pool_desc(pool_a, layers, pages, Hkv, w.dtype)
+    db = mc.pool_desc(pool_b, layers, pages, Hkv, w.dtype)
+    q = torch.randn(tq * Hq * 128, dtype=torch.bfloat16, device=dev)
+    k = torch.randn(tq * Hkv * 128, dtype=torch.bfloat16, device=dev)
+    v = torch.randn(tq * Hkv * 128, dtype=torch.bfloat16, device=dev)
+    cu_q, begin = up(w.cu_q), up(w.b.astype(np.int32))
+    cu_pages = up(w.cu_pages)
+    table_a, table_b = up(np.concatenate(tab_a).astype(np.int32)), up(np.concatenate(tab_b).astype(np.int32))
+    s0, s1 = up(np.zeros(B, np.int32)), up(w.n.astype(np.int32))
+    sizes = np.array([2 * int(t) * Hkv * 128 * 2 for t in w.n], dtype=np.int64)      # bytes
+    off = up(np.concatenate([[0], np.cumsum(sizes)[:-1]]))
+    sends = [torch.empty(int(sizes.sum()) // 2, dtype=torch.int16, device=dev) for _ in range(layers)]
+    max_pages = int(max(-(-int(t) // 16) for t in w.n))
+    wsb = mc.mc_attn_workspace_size(B, tq, Hq, Hkv)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    out = torch.empty((tq, Hq, 128), dtype=torch.int16, device=dev)
+    lse = torch.empty((tq, Hq), dtype=torch.float32, device=dev)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    mc.mc_attn_plan(da, Hq, B, tq, cu_q, begin, table_a, cu_pages, ws, wsb)   # once for all layers
+
+    def one_pass(overlap, attn_ev):
+        xfer = side if overlap else main
+        for layer in range(layers):
+            mc.mc_kv_append(da, layer, k, v, B, tq, cu_q, begin, table_a, cu_pages, stream=main)
+            appended = torch.cuda.Event()
+            appended.record(main)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+            mc.mc_prefix_prefill_attn(da, layer, q, Hq, B, tq, cu_q, begin, table_a, cu_pages, 0.0,
+                                      out, lse, ws, wsb, stream=main)
+            e1.record(main)
+            attn_ev.append((e0, e1))
+            if overlap:                 # the layer's KV is in the pages: it may leave
+                side.wait_event(appended)
+            mc.mc_kv_pack_batch(da, layer, layer + 1, B, table_a, cu_pages, s0, s1, off, max_pages,
+                                sends[layer], stream=xfer)
+            mc.mc_kv_unpack_batch(db, layer, layer + 1, B, table_b, cu_pages, s0, s1, off,
+                                  max_pages, sends[layer], stream=xfer)
+        if overlap:
+            main.wait_stream(side)
+
+    res = {}
+    for overlap in (False, True):
+        totals, attn = [], []
+        for it in range(iters + 1):
+            ev, t0, t1 = [], torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0.record(main)
+            one_pass(overlap, ev)
+            t1.record(main)
+            torch.cuda.synchronize()
+            if it:                                       # the first pass warms up
+                totals.append(t0.elapsed_time(t1))
+                attn += [a.elapsed_time(b) for a, b in ev]
+        key = "two_streams" if overlap else "one_stream"
+        res[key] = {"pass_ms_median": round(float(np.median(totals)), 4),
+                    "pass_ms_min": round(float(np.min(totals)), 4),
+                    "attention_ms_median": round(float(np.median(attn)), 4),
+                    "attention_ms_min": round(float(np.min(attn)), 4)}
+    res["layers"] = layers
+    res["payload_MiB_per_layer"] = round(n_tok * w.token_bytes / 2**20, 1)
+    res["pass_gain"] = round(res["one_stream"]["pass_ms_median"] / res["two_streams"]["pass_ms_median"], 3)
+    res["attention_slowdown_beside_transfer"] = round(
+        res["two_streams"]["attention_ms_median"] / res["one_stream"]["attention_ms_median"], 3)
+    del pool_a, pool_b, sends, q, k, v, ws, out, lse
     torch.cuda.empty_cache()
     return res
 
@@ -209,6 +358,9 @@ def main():
     ap.add_argument("--attention-only", metavar="WORKLOAD", default=None,
                     help="time only the attention kernel on one workload and exit (for profiling): "
                          + ", ".join(ATTN_WORKLOADS))
+    ap.add_argument("--decode-step", metavar="WORKLOAD", default=None,
+                    help="time only one decode step (append + plan + attention + merge), launched "
+                         "call by call, from a HIP graph and with a plan made once, and exit")
     ap.add_argument("--values", choices=["normal", "zero"], default="normal",
                     help="with --attention-only: Q/K/V values, N(0,1) or all zeros")
     args = ap.parse_args()
@@ -220,6 +372,7 @@ def main():
     import numpy as np
     import torch
 
+    import bench_probe
     import mc_inputs as mi
     import paper_2412_12488_amd as mc
 
@@ -229,6 +382,10 @@ def main():
     if args.attention_only:
         print(json.dumps(attention_only(args.attention_only, max(1, min(args.steps, 20)),
                                         args.values)))
+        return
+    if args.decode_step:
+        print(json.dumps({args.decode_step: decode_step_latency(args.decode_step,
+                                                                max(1, min(args.steps, 50)))}))
         return
 
     def up(a):
@@ -338,7 +495,8 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in attn_events]))
+    attn_times = np.array([a.elapsed_time(b) for a, b in attn_events])
+    attn_ms = float(attn_times.mean())
     attn_tflops = flops / (attn_ms * 1e-3) / 1e12
     value = flops / (ms_per_step * 1e-3) / 1e12
 
@@ -360,30 +518,44 @@ def main():
         fl = [0]
 
         def go():
-            fl[0] = mc.mc_mfma_probe(w.dtype, operands, 512, 1000, sink)
+            fl[0] = bench_probe.mfma_probe(w.dtype, operands, 512, 1000, sink,
+                                           torch.cuda.current_stream().cuda_stream)
         ms = timed(go, iters=5, warm=2)
         return round(fl[0] / ms / 1e9, 1)
 
-    n_op = mc.mc_mfma_probe_operand_bytes() // 2
+    n_op = bench_probe.operand_bytes() // 2
     ops_const = torch.full((n_op,), 1.0, dtype=torch.bfloat16, device=dev)
     ops_normal = up(mi.normal_bits(mi.rng_for(args.seed, 91), n_op, w.dtype))
     mfma_measured = {"constant_operands_TFLOPs": mfma_rate(ops_const),
                      "normal_operands_TFLOPs": mfma_rate(ops_normal)}
     del ops_const, ops_normal
 
-    # ---- the attention call on the paper's Table-2 shapes and on decode steps (one new token
-    #      per sequence, alone and fused with a prefill range): the planner cuts their KV
-    #      ranges into chunks; decode is bound by HBM, so its figure is algorithmic GB/s ----
-    other = {}
+    # ---- the attention call alone on the other configs (each with a sample of its outputs
+    #      checked against the CPU oracle), on the paper's Table-2 shapes and on decode steps (one
+    #      new token per sequence, alone and fused with a prefill range): the planner cuts the
+    #      KV ranges of the small launches into chunks; decode is bound by HBM, so its figure is
+    #      algorithmic GB/s ----
+    other, overlap = {}, None
     if not args.no_copy_sweep:
+        ceiling = mfma_measured["normal_operands_TFLOPs"]
+        for name in ("cfg3-passB", "cfg4", "cfg5-16k", "cfg5-32k"):
+            r = attention_only(name, 10, oracle_triples=0 if args.no_cpu_baseline else 1024,
+                               mfma_ceiling=ceiling)
+            other[name] = {k: r[k] for k in ("ms", "ms_median", "ms_min", "TFLOPs",
+                                             "frac_of_mfma_peak", "frac_of_measured_mfma_rate",
+                                             "useful_flops") if k in r}
+            if "oracle_sample" in r:
+                other[name]["oracle_sample"] = r["oracle_sample"]
         for name in ("paper-500-over-500", "paper-500-over-2500", "paper-500-over-4500",
                      "decode-64", "decode-256", "decode-64-plus-prefill", "decode-64-no-forks",
                      "decode-64-forks"):
             r = attention_only(name, 10)
-            other[name] = {"ms": r["ms"], "TFLOPs": r["TFLOPs"],
-                           "algorithmic_GBps": r["algorithmic_GBps"]}
+            other[name] = {"ms": r["ms"], "ms_median": r["ms_median"], "ms_min": r["ms_min"],
+                           "TFLOPs": r["TFLOPs"], "algorithmic_GBps": r["algorithmic_GBps"]}
         # a whole decode step (append + plan + attention + merge), call by call and as a graph
         other["decode_step_us"] = {n: decode_step_latency(n) for n in ("decode-8", "decode-64")}
+        # four layers, each layer's KV shipped to a second pool after or beside the next layer
+        overlap = layer_overlap(w, 4)
 
     # ---- copies, each alone: this workload, then the long-context transfer size ----
     copy = {}
@@ -428,6 +600,34 @@ def main():
         desc_b, 0, 1, B, table_b, cu_pages_b, r_s0, r_s1, send_off, max_range_pages,
         send_all)) / 1e6, 1)
     copy["payload_MiB"] = round(kv_bytes / 2**20, 1)
+    # the same three copies with the pages, the new K/V and the transfer buffer changing from
+    # launch to launch (six sets, about 0.9 GiB touched per round): nothing a launch reads or
+    # writes can still sit in the 256 MiB Infinity Cache from the launch before
+    R = 6
+    rot_tables = [up(np.concatenate(mi.scatter_page_tables(mi.rng_for(args.seed, 400 + r),
+                                                           w.num_pages, w.n)).astype(np.int32))
+                  for r in range(R)]
+    rot_send = [torch.empty_like(send_all) for _ in range(R)]
+    rot_k = [torch.empty_like(k_new).copy_(k_new) for _ in range(R)]
+    rot_v = [torch.empty_like(v_new).copy_(v_new) for _ in range(R)]
+    turn = [0]
+
+    def rotated(fn):
+        def go():
+            r = turn[0] = (turn[0] + 1) % R
+            fn(r)
+        return timed(go, iters=4 * R, warm=R)
+    copy["rotated"] = {
+        "sets": R,
+        "append_GBps": round(2 * new_bytes / rotated(lambda r: mc.mc_kv_append(
+            desc_a, 0, rot_k[r], rot_v[r], B, total_q, cu_q, begin, rot_tables[r], cu_pages)) / 1e6, 1),
+        "pack_batch_GBps": round(2 * kv_bytes / rotated(lambda r: mc.mc_kv_pack_batch(
+            desc_a, 0, 1, B, rot_tables[r], cu_pages, r_s0, r_s1, send_off, max_range_pages,
+            rot_send[r])) / 1e6, 1),
+        "unpack_batch_GBps": round(2 * kv_bytes / rotated(lambda r: mc.mc_kv_unpack_batch(
+            desc_b, 0, 1, B, rot_tables[r], cu_pages_b, r_s0, r_s1, send_off, max_range_pages,
+            rot_send[r])) / 1e6, 1)}
+    del rot_send, rot_k, rot_v
     # one layer of a 1000 / 3000 / 5000-token sequence out of one pool and into another (the
     # paper's Table 2 transfers, there with the wire): microseconds for pack + unpack
     t2 = {}
@@ -457,8 +657,9 @@ def main():
         ta = up(mi.rng_for(args.seed, 78).permutation(npg).astype(np.int32))
         tb = up(mi.rng_for(args.seed, 79).permutation(npg).astype(np.int32))
         payload = L * T * w.token_bytes
-        ms_p = timed(lambda: mc.mc_kv_pack_range(da, 0, L, ta, npg, 0, T, big_s), iters=10)
-        ms_u = timed(lambda: mc.mc_kv_unpack_range(dbb, 0, L, tb, npg, 0, T, big_s), iters=10)
+        st_p = launch_stats(lambda: mc.mc_kv_pack_range(da, 0, L, ta, npg, 0, T, big_s), 10, 3)
+        st_u = launch_stats(lambda: mc.mc_kv_unpack_range(dbb, 0, L, tb, npg, 0, T, big_s), 10, 3)
+        ms_p, ms_u = st_p["mean"], st_u["mean"]
         ms_c = timed(lambda: big_b.copy_(big_a), iters=10)
         copy["long_context"] = {
             "payload_GiB": payload / 2**30,
@@ -466,30 +667,83 @@ def main():
             "unpack_GBps": round(2 * payload / ms_u / 1e6, 1),
             "pack_frac_of_hbm_peak": round(2 * payload / ms_p / 1e6 / HBM_PEAK_GBS, 3),
             "unpack_frac_of_hbm_peak": round(2 * payload / ms_u / 1e6 / HBM_PEAK_GBS, 3),
+            "pack_ms": {k: round(v, 4) for k, v in st_p.items()},
+            "unpack_ms": {k: round(v, 4) for k, v in st_u.items()},
             "plain_copy_GBps": round(2 * payload / ms_c / 1e6, 1),
         }
         del big_a, big_b, big_s
 
-    # ---- CPU oracle on this machine's host cores, bounded sample of the same workload ----
-    cpu = None
+    # ---- CPU oracle on this machine's host cores: the attention of the whole workload on all
+    #      cores (also the reference for the error of the last step's output), a sample of it
+    #      on one core, and the copies ----
+    cpu, parity = None, None
     if not args.no_cpu_baseline:
+        import ctypes
+
         import oracle
         shape = oracle.Shape(1, w.num_pages, 16, Hkv, D, w.dtype)
         opool = oracle.new_pool(shape)
+        c0 = time.perf_counter()
         for s in range(B):
             oracle.append(opool, shape, 0, kv[s][0], kv[s][1], 0, w.page_tables[s])
+        t_append = time.perf_counter() - c0
         cores = len(os.sched_getaffinity(0))
         omp = int(os.environ.get("OMP_NUM_THREADS", cores))
-        t_cpu = 0.0
+        t_cpu, err_o, err_l = 0.0, 0.0, 0.0
+        out_h, lse_h = out.cpu().numpy().view(np.uint16), lse.cpu().numpy().astype(np.float64)
         for s in range(B):
             qs = w.q(s)
             c0 = time.perf_counter()
-            oracle.attention(opool, shape, 0, w.page_tables[s], qs, Hq, int(w.b[s]), int(w.n[s]))
+            ro, rl = oracle.attention(opool, shape, 0, w.page_tables[s], qs, Hq, int(w.b[s]),
+                                      int(w.n[s]))
             t_cpu += time.perf_counter() - c0
+            lo, hi = int(w.cu_q[s]), int(w.cu_q[s + 1])
+            err_o = max(err_o, float(np.max(np.abs(oracle.decode(out_h[lo:hi], w.dtype) - ro))))
+            err_l = max(err_l, float(np.max(np.abs(lse_h[lo:hi] - rl))))
+        parity = {"rows": "every row and q head of the timed workload",
+                  "max_abs_err_O": round(err_o, 6), "max_abs_err_LSE": round(err_l, 8)}
+        # one core: 4096 sampled (row, head) pairs of the longest sequence
+        gomp = ctypes.CDLL("libgomp.so.1")
+        s_long = int(np.argmax(w.n))
+        rows, heads = mi.sample_rows(mi.rng_for(args.seed, 93), int(w.n[s_long] - w.b[s_long]),
+                                     int(w.b[s_long]), Hq, 4096, 32, num_kv_heads=Hkv)
+        fl_one = int(np.sum(4 * D * (int(w.b[s_long]) + rows.astype(np.int64) + 1)))
+        gomp.omp_set_num_threads(1)
+        c0 = time.perf_counter()
+        oracle.attention(opool, shape, 0, w.page_tables[s_long], w.q(s_long), Hq, int(w.b[s_long]),
+                         int(w.n[s_long]), sel_rows=rows, sel_heads=heads)
+        t_one = time.perf_counter() - c0
+        gomp.omp_set_num_threads(min(cores, omp))
+        # copies: pack of every sequence out of the pool, unpack into a second one
+        opool_b = oracle.new_pool(shape)
+        c0 = time.perf_counter()
+        bufs = [oracle.pack(opool, shape, 0, 1, w.page_tables[s], 0, int(w.n[s])) for s in range(B)]
+        t_pack = time.perf_counter() - c0
+        c0 = time.perf_counter()
+        for s in range(B):
+            oracle.unpack(opool_b, shape, 0, 1, tables_b_np[s], 0, int(w.n[s]), bufs[s])
+        t_unpack = time.perf_counter() - c0
         cpu = {"value": round(flops / t_cpu / 1e12, 6), "unit": "TFLOP/s",
                "cores": min(cores, omp), "kind": "oracle",
                "sample": f"attention of the whole workload (all {total_q} new rows x {Hq} heads, "
-                         f"{B} sequences), fp64 C/OpenMP oracle, {t_cpu:.1f} s; copies not timed"}
+                         f"{B} sequences), fp64 C/OpenMP oracle, {t_cpu:.1f} s",
+               "one_core": {"value": round(fl_one / t_one / 1e12, 6), "unit": "TFLOP/s",
+                            "sample": f"{rows.size} sampled (row, head) pairs of the longest "
+                                      f"sequence, {t_one:.1f} s",
+                            "whole_workload_s_extrapolated": round(t_one * flops / fl_one, 1)},
+               "copies_GBps": {"append": round(2 * kv_bytes / t_append / 1e9, 2),
+                               "pack": round(2 * kv_bytes / t_pack / 1e9, 2),
+                               "unpack": round(2 * kv_bytes / t_unpack / 1e9, 2),
+                               "note": "whole workload, one thread (per-token memcpy loops)"}}
+
+    # what the oracle would need for each other config at the rate it reached on this one
+    if cpu and other:
+        for name, r in other.items():
+            if isinstance(r, dict) and "useful_flops" in r:
+                r["oracle_whole_workload_s_extrapolated"] = {
+                    f"{cpu['cores']}_cores": round(r["useful_flops"] / (cpu["value"] * 1e12), 1),
+                    "one_core": round(r["useful_flops"] / (cpu["one_core"]["value"] * 1e12), 1),
+                    "basis": "extrapolated from the oracle's measured rate on the timed workload"}
 
     result = {
         "metric": "prefix-prefill attention TFLOP/s (% MFMA peak); KV pack/unpack GB/s (% HBM)",
@@ -520,15 +774,30 @@ def main():
                      if args.seed == MEASURED_TRAFFIC["seed"] else None,
                      "algorithmic_bytes": 2 * total_q * Hq * D * 2 + total_q * Hq * 4
                      + int(np.sum(w.n)) * w.token_bytes,
-                     "avg_launch_ms": round(attn_ms, 4)},
+                     "traffic_source": "rocprofv3 FETCH_SIZE + WRITE_SIZE of this command with seed "
+                                       "2000 (profiles/bench_cfg2_hbm_traffic.md), not measured "
+                                       "in this run",
+                     "avg_launch_ms": round(attn_ms, 4),
+                     "median_launch_ms": round(float(np.median(attn_times)), 4),
+                     "min_launch_ms": round(float(attn_times.min()), 4),
+                     "frac_of_measured_mfma_rate": round(
+                         attn_tflops / mfma_measured["normal_operands_TFLOPs"], 4),
+                     "target_frac": 0.5, "target_met": bool(attn_tflops / MFMA_PEAK_TFLOPS >= 0.5)},
         "roofline_copy": None if args.no_copy_sweep else {
             "kernel": "range_copy_kernel<pack>, 32 layers x 32768 tokens", "bound": "hbm",
             "achieved": copy["long_context"]["pack_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": copy["long_context"]["pack_frac_of_hbm_peak"],
             "traffic": MEASURED_TRAFFIC["pack_4GiB_bytes"],
-            "algorithmic_bytes": 2 * int(copy["long_context"]["payload_GiB"] * 2**30)},
+            "traffic_source": "rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/), not measured in "
+                              "this run",
+            "algorithmic_bytes": 2 * int(copy["long_context"]["payload_GiB"] * 2**30),
+            "target_frac": 0.7,
+            "target_met_pack": bool(copy["long_context"]["pack_frac_of_hbm_peak"] >= 0.7),
+            "target_met_unpack": bool(copy["long_context"]["unpack_frac_of_hbm_peak"] >= 0.7)},
         "copy": copy,
         "attention_other_workloads": other or None,
+        "layer_overlap": overlap,
+        "parity_in_this_run": parity,
         "cpu_baseline": cpu,
     }
     print(json.dumps(result))

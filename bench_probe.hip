@@ -1,10 +1,14 @@
+// Measurement aid of bench.py, not part of the KV-cache library: built into libbench_probe.so
+// beside this file (bench_probe.py).
 // Calibration kernel for the attention roofline: the rate at which this GPU issues the MFMA
 // instruction the attention kernel is built on (v_mfma_f32_32x32x16 with 2-byte operands),
 // with nothing else going on, on operand values supplied by the caller.  The rate depends on
 // those values: the matrix pipes draw more power the more operand bits change from one
 // instruction to the next, and the clock follows.  Constant operands show the nominal rate;
 // operands drawn like the workload's show what a kernel working on such data can reach.
-#include "mc_common.h"
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
 namespace {
 
@@ -63,18 +67,24 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(const u32x4* 
 
 extern "C" {
 
-size_t mc_mfma_probe_operand_bytes(void) {
+// bytes of operand values a launch reads
+size_t bench_mfma_probe_operand_bytes(void) {
   return (size_t)2 * kFrags * 16 * kProbeThreads * sizeof(u32x4);   // 1 MiB
 }
 
-mc_status mc_mfma_probe(mc_dtype dtype, const void* operands, int32_t blocks, int32_t iters,
-                        float* sink, int64_t* flops_out, void* stream) {
-  if (!operands || !sink || !mc::aligned16(operands) || blocks <= 0 || iters <= 0)
-    return MC_ERR_INVALID;
-  if (dtype != MC_F16 && dtype != MC_BF16) return MC_ERR_UNSUPPORTED;
+// Launches `blocks` workgroups of 4 wavefronts that each issue iters x 64 MFMAs on fragments read
+// from `operands` (device, bench_mfma_probe_operand_bytes() bytes of 2-byte values: dtype 0 =
+// fp16, 1 = bf16).  sink: device, blocks x 256 floats, overwritten.  *flops_out (host, may be
+// NULL): floating-point operations issued.  Asynchronous on `stream`; the caller times it.
+// Returns 0, or 1 on bad arguments, 2 if the launch failed.
+int32_t bench_mfma_probe(int32_t dtype, const void* operands, int32_t blocks, int32_t iters,
+                         float* sink, int64_t* flops_out, void* stream) {
+  if (!operands || !sink || (reinterpret_cast<uintptr_t>(operands) & 15u) || blocks <= 0 ||
+      iters <= 0 || (dtype != 0 && dtype != 1))
+    return 1;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const u32x4* ops = static_cast<const u32x4*>(operands);
-  if (dtype == MC_F16)
+  if (dtype == 0)
     hipLaunchKernelGGL(mfma_probe_kernel<f16x8>, dim3(blocks), dim3(kProbeThreads), 0, hs, ops,
                        iters, sink);
   else
@@ -82,7 +92,7 @@ mc_status mc_mfma_probe(mc_dtype dtype, const void* operands, int32_t blocks, in
                        iters, sink);
   if (flops_out)   // 32 x 32 x 16 multiply-adds per instruction
     *flops_out = (int64_t)blocks * (kProbeThreads / 64) * iters * 64 * (2ll * 32 * 32 * 16);
-  return mc::launch_status();
+  return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
 }  // extern "C"

@@ -369,24 +369,6 @@ mc_status mc_prefix_index_match(void* index, const int32_t* tokens /* host */, i
 mc_status mc_prep_recv(void* index, void* alloc, const int32_t* prompt /* host */, int32_t end,
                        int32_t* pages_out /* host */, int32_t* match_len_out);
 
-/* ---- calibration: MFMA issue rate ------------------------------------------
- * Not a step of the paper's path: a measurement aid for the attention roofline
- * (the attention of Sec. 3.4 is a dense contraction on v_mfma_f32_32x32x16 with
- * 2-byte operands).  Launches `blocks` workgroups of 4 wavefronts that each issue
- * iters x 64 such instructions on operand fragments read from `operands`
- * (device, mc_mfma_probe_operand_bytes() bytes of 2-byte values of `dtype`,
- * caller-owned and caller-filled: constant values show the nominal rate, values
- * distributed like the workload's show the rate such data allows, since the
- * matrix pipes' power and with it the clock depend on the operand bits).
- * sink: device, blocks x 256 floats, overwritten.  *flops_out (host, may be NULL)
- * receives the floating-point operations issued.  Asynchronous on `stream`; the
- * caller times it.  Errors: MC_ERR_INVALID (null/misaligned pointers, counts
- * <= 0), MC_ERR_UNSUPPORTED (dtype). */
-size_t mc_mfma_probe_operand_bytes(void);
-mc_status mc_mfma_probe(mc_dtype dtype, const void* operands /* device */, int32_t blocks,
-                        int32_t iters, float* sink /* device */, int64_t* flops_out /* host */,
-                        void* stream);
-
 #ifdef __cplusplus
 }
 #endif

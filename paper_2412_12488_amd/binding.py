@@ -19,7 +19,6 @@ EXPORTS = [
     "mc_kv_append", "mc_kv_append_send", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_ahead", "mc_attn_plan_check",
     "mc_prefix_prefill_attn", "mc_prefix_prefill_attn_noalloc", "mc_kv_pack_range", "mc_kv_unpack_range",
     "mc_kv_pack_batch", "mc_kv_unpack_batch",
-    "mc_mfma_probe_operand_bytes", "mc_mfma_probe",
     "mc_plan_remote_send", "mc_addr_compress", "mc_addr_expand",
     "mc_prefix_index_create", "mc_prefix_index_destroy", "mc_prefix_index_insert",
     "mc_prefix_index_match", "mc_prep_recv", "mc_kv_fork_sequence", "mc_kv_copy_page",
@@ -82,9 +81,6 @@ def lib():
     L.mc_kv_unpack_range.argtypes = [pd, i32, i32, vp, i32, i32, i32, vp, vp]
     L.mc_kv_pack_batch.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
     L.mc_kv_unpack_batch.argtypes = [pd, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
-    L.mc_mfma_probe_operand_bytes.argtypes = []
-    L.mc_mfma_probe_operand_bytes.restype = sz
-    L.mc_mfma_probe.argtypes = [i32, vp, i32, i32, vp, C.POINTER(i64), vp]
     L.mc_plan_remote_send.argtypes = [i32, i32, i32, i32, C.POINTER(mc_send_plan)]
     L.mc_addr_compress.argtypes = [C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i32)]
     L.mc_addr_expand.argtypes = [C.POINTER(i32), i32, C.POINTER(i32), i32, C.POINTER(i32)]
@@ -262,18 +258,6 @@ def mc_kv_unpack_batch(pool: mc_pool_desc, layer_begin, layer_end, batch, page_t
                                     _ptr(page_table), _ptr(cu_pages), _ptr(s0), _ptr(s1),
                                     _ptr(buf_offset), max_range_pages, _ptr(sendbuf),
                                     _stream(stream)), "mc_kv_unpack_batch")
-
-
-def mc_mfma_probe_operand_bytes() -> int:
-    return int(lib().mc_mfma_probe_operand_bytes())
-
-
-def mc_mfma_probe(dtype, operands, blocks, iters, sink, stream=None) -> int:
-    """Launches the calibration kernel; returns the floating-point operations it issues."""
-    flops = C.c_int64(0)
-    _check(lib().mc_mfma_probe(dtype, _ptr(operands), blocks, iters, _ptr(sink), C.byref(flops),
-                               _stream(stream)), "mc_mfma_probe")
-    return int(flops.value)
 
 
 def mc_plan_remote_send(sender_match, receiver_match, begin, end) -> dict:

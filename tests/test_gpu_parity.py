@@ -323,22 +323,6 @@ def test_paper_shaped_points():
         check_attention(mi.paper_point(cached))
 
 
-@pytest.mark.gpu
-def test_mfma_probe_counts_and_runs():
-    """The calibration kernel: constant operands 1.0 make every accumulator element equal to the
-    number of multiply-adds along k, so the sink holds 16 x (iters x 64 / 4 chains) x 16 x 4."""
-    n = mc.mc_mfma_probe_operand_bytes() // 2
-    ops = torch.full((n,), 1.0, dtype=torch.bfloat16, device="cuda:0")
-    sink = torch.zeros(8 * 256, dtype=torch.float32, device="cuda:0")
-    iters = 3
-    flops = mc.mc_mfma_probe(mc.MC_BF16, ops, 8, iters, sink)
-    torch.cuda.synchronize()
-    assert flops == 8 * 4 * iters * 64 * 2 * 32 * 32 * 16
-    # per lane: 4 accumulators x 16 elements, each = (iters * 64 / 4) instructions x 16 products
-    expect = 4 * 16 * (iters * 64 // 4) * 16
-    assert torch.all(sink == float(expect)), (sink[:4], expect)
-
-
 # ------------------------------------------------- cut KV ranges (decode rows, short batches) ----
 def plan_header(w):
     pool = DevPool(w)

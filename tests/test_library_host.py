@@ -174,17 +174,6 @@ def test_workspace_size():
     assert s2 > s1 and s1 % 16 == 0
 
 
-def test_mfma_probe_validation():
-    assert mc.mc_mfma_probe_operand_bytes() == 1 << 20
-    pr = mc.mc_mfma_probe
-    assert _status(pr, mc.MC_BF16, None, 4, 1, FAKE) == mc.MC_ERR_INVALID
-    assert _status(pr, mc.MC_BF16, FAKE, 4, 1, None) == mc.MC_ERR_INVALID
-    assert _status(pr, mc.MC_BF16, FAKE + 2, 4, 1, FAKE) == mc.MC_ERR_INVALID
-    assert _status(pr, mc.MC_BF16, FAKE, 0, 1, FAKE) == mc.MC_ERR_INVALID
-    assert _status(pr, mc.MC_BF16, FAKE, 4, 0, FAKE) == mc.MC_ERR_INVALID
-    assert _status(pr, 7, FAKE, 4, 1, FAKE) == mc.MC_ERR_UNSUPPORTED
-
-
 def _as_range(tokens, empty_at):
     if not tokens:
         return (empty_at, empty_at)
