@@ -26,7 +26,8 @@ HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
 
 ATTN_WORKLOADS = ["cfg2", "cfg3-passB", "cfg4", "cfg5-16k", "cfg5-32k", "paper-500-over-500",
                   "paper-500-over-2500", "paper-500-over-4500", "decode-8", "decode-64",
-                  "decode-256", "decode-64-plus-prefill", "decode-64-forks", "decode-64-no-forks"]
+                  "decode-256", "decode-64-plus-prefill", "decode-64-forks", "decode-64-no-forks",
+                  "short-64-forks", "short-64-no-forks"]
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very
 # command with the default seed (counters scaled by what a plain 4 GiB copy reads; see
@@ -55,13 +56,26 @@ def attention_workload(name):
         return mi.paper_point(int(name.rsplit("-", 1)[1]))
     if name in ("decode-64-forks", "decode-64-no-forks"):
         # 64 decode steps of sequences that continue one 2048-token prompt by 64..1024 tokens of
-        # their own: as forks (page tables share the prompt's 128 pages, Sec. 3.4 fork_sequence)
+        # their own: as forks (page tables share the prompt's 128 pages, Sec. 3.5 fork_sequence)
         # or as unrelated sequences of the same lengths
         rng = mi.rng_for(4243)
         n = 2048 + rng.integers(64, 1025, size=64)
         w = mi.Workload(name, 4243, mi.BF16, 1, 32, 8, 65536, n, n - 1)
         w.page_tables = mi.scatter_page_tables(mi.rng_for(4243, mi.KIND_TABLE), 65536, n)
         if name == "decode-64-forks":
+            for s in range(1, 64):
+                w.share_prefix(s, 0, 2048)
+        return w
+    if name in ("short-64-forks", "short-64-no-forks"):
+        # 64 sequences that continue one 2048-token prompt by 0..512 cached tokens of their own
+        # and bring 5..24 new tokens each (speculative or chunked continuation of forked
+        # requests): as forks of the prompt, or as unrelated sequences of the same lengths
+        rng = mi.rng_for(4244)
+        b = 2048 + rng.integers(0, 513, size=64)
+        n = b + rng.integers(5, 25, size=64)
+        w = mi.Workload(name, 4244, mi.BF16, 1, 32, 8, 65536, n, b)
+        w.page_tables = mi.scatter_page_tables(mi.rng_for(4244, mi.KIND_TABLE), 65536, n)
+        if name == "short-64-forks":
             for s in range(1, 64):
                 w.share_prefix(s, 0, 2048)
         return w
@@ -441,7 +455,7 @@ def main():
 
     # With --overlap, two streams (both at the default priority).  main: append -> attention.
     # side: plan (needs nothing from the step), then pack + unpack of the layer's KV as soon as
-    # the append is done, beside the attention (Sec. 3.5: a layer's KV is sent while the
+    # the append is done, beside the attention (Sec. 3.6: a layer's KV is sent while the
     # computation goes on).
     args.serial = not args.overlap
     main_s = torch.cuda.current_stream()
@@ -548,7 +562,7 @@ def main():
                 other[name]["oracle_sample"] = r["oracle_sample"]
         for name in ("paper-500-over-500", "paper-500-over-2500", "paper-500-over-4500",
                      "decode-64", "decode-256", "decode-64-plus-prefill", "decode-64-no-forks",
-                     "decode-64-forks"):
+                     "decode-64-forks", "short-64-no-forks", "short-64-forks"):
             r = attention_only(name, 10)
             other[name] = {"ms": r["ms"], "ms_median": r["ms_median"], "ms_min": r["ms_min"],
                            "TFLOPs": r["TFLOPs"], "algorithmic_GBps": r["algorithmic_GBps"]}

@@ -15,12 +15,13 @@
  *     prefills prompt[begin:] over the cached prompt[:begin], Sec. 3.1; the
  *     balanced split continues with prompt[s:], fused with the decode steps
  *     of other sequences, Sec. 3.3; sequences forked from one prompt share its
- *     pages, Sec. 3.4)
+ *     pages, Sec. 3.4 and fork_sequence in Sec. 3.5)
  *                                   -> mc_kv_append, mc_prefix_prefill_attn
  *   - remote_send moves the KV of prompt[begin:end] into the entries the
- *     receiver reserved (Sec. 3.1, Sec. 3.5); on one GPU the wire is replaced
- *     by a contiguous buffer in HBM; which ranges the sender copies, computes
- *     and sends follows from what the two engines have cached (Sec. 3.4)
+ *     receiver reserved (Sec. 3.1), layer by layer beside the computation
+ *     (Sec. 3.6); on one GPU the wire is replaced by a contiguous buffer in HBM;
+ *     which ranges the sender copies, computes and sends follows from what the
+ *     two engines have cached (Sec. 3.5, Cases 1 and 2)
  *            -> mc_plan_remote_send, mc_kv_pack_range, mc_kv_unpack_range
  *
  * The paper fixes no dtype, page size, page layout, softmax scale or LSE base;
@@ -39,8 +40,8 @@
  *   - Values that live in device arrays (page ids, offsets) cannot be seen by
  *     the host.  Kernels bounds-check every page id against the pool and every
  *     page-table index against the sequence's table; an entry that fails is
- *     skipped (no read, no write) and, for attention, reported through
- *     mc_attn_plan_check.
+ *     skipped (no read, no write) and reported: for attention through
+ *     mc_attn_plan_check, for the copies through mc_kv_copy_check.
  *   - Return value: mc_status (MC_OK = 0).
  *
  * Layouts (2-byte elements, fp16 or bf16, head_dim D = 128, page size P = 16)
@@ -90,6 +91,7 @@ typedef struct {
   int32_t num_kv_heads;
   int32_t head_dim;     /* must be 128 */
   int32_t dtype;        /* mc_dtype */
+  int32_t* skipped;     /* device int32 counter, 4-byte aligned, or NULL: see mc_kv_copy_check */
 } mc_pool_desc;
 
 /* Human-readable name of a status code (static storage). */
@@ -97,7 +99,7 @@ const char* mc_status_string(int32_t status);
 /* Bumped on any incompatible change of this header. */
 int32_t mc_abi_version(void);
 
-/* ---- page allocator (prep_recv "allocates KV cache entries", Sec. 3.1) ----
+/* ---- page allocator (prep_recv reserves the entries that will receive KV, Sec. 3.1) ----
  * Host-only LIFO free list over page ids [0, num_pages).  A fresh allocator
  * hands out 0, 1, 2, ...; freed pages are pushed in argument order, so the last
  * page of the last free call is handed out next.  Not thread-safe. */
@@ -112,9 +114,26 @@ mc_status mc_kv_allocator_num_free(void* alloc, int32_t* num_free_out /* host */
  * id is outside [0,num_pages), MC_ERR_ALIAS if one appears twice, else MC_OK. */
 mc_status mc_kv_check_page_table(const int32_t* pages /* host */, int64_t n, int32_t num_pages);
 
+/* ---- what the copy kernels skipped -------------------------------------------
+ * append, append_send, pack and unpack (single and batched) never read or write
+ * out of bounds: a token whose table index lies beyond its sequence's table or
+ * whose page id lies outside the pool, and a sequence of a batched call whose
+ * offsets are malformed (negative or reversed table offsets, negative or
+ * misaligned buffer offset), is left out.  With pool->skipped set, every kernel
+ * adds the number of units it left out for such a reason (tokens for append,
+ * pages or sequences for pack / unpack) to that counter; ranges that are empty
+ * by their own statement (s0 >= s1) are not counted.  The caller zeroes the
+ * counter before first use (it is only ever added to).
+ * mc_kv_copy_check synchronises `stream`, reads the counter into *skipped_out
+ * (host, may be NULL), sets it back to zero and returns MC_OK if it was zero,
+ * MC_ERR_RANGE otherwise; MC_ERR_INVALID without a counter.  Like
+ * mc_attn_plan_check it blocks; the copy calls themselves never do. */
+mc_status mc_kv_copy_check(const mc_pool_desc* pool, int32_t* skipped_out /* host */,
+                           void* stream);
+
 /* ---- append: write new K/V into their (page, slot) entries -----------------
- * (the KV-write half of attention(qkv_data), Sec. 3.4; "new KVs are first
- * materialized through prefill computation", Sec. 3.1).
+ * (the KV-write half of attention(qkv_data), Sec. 3.4; remote_send computes the KV
+ * it does not hold before it sends them, Sec. 3.1).
  * Token g of sequence s (cu_q[s] <= g < cu_q[s+1]) has position
  * pos = begin[s] + g - cu_q[s] and goes to page page_table[cu_pages[s] + pos/16],
  * slot pos%16, of `layer`.  No other byte of the pool is written.  Two tokens
@@ -130,8 +149,8 @@ mc_status mc_kv_append(const mc_pool_desc* pool, int32_t layer,
                        const int32_t* cu_pages /* device [batch+1] */,
                        void* stream);
 
-/* mark_send (Sec. 3.4: KV marked for sending leaves while the computation goes
- * on, layer by layer, Sec. 3.5): mc_kv_append, and in the same pass the tokens of
+/* mark_send (Sec. 3.4; with it set, attention also sends the sequence's KV, Sec. 3.5,
+ * layer by layer while the computation goes on, Sec. 3.6): mc_kv_append, and in the same pass the tokens of
  * the new range that lie in the marked range [s0[s], s1[s]) of their sequence
  * are written to the sequence's slice of a transfer buffer as well - the bytes
  * mc_kv_pack_batch(pool, send_layer_begin, ..., s0, s1, buf_offset, ...) would
@@ -162,7 +181,7 @@ mc_status mc_kv_append_send(const mc_pool_desc* pool, int32_t layer,
  * including the new range, are read from the pages (mc_kv_append of this layer
  * comes first on the same stream).  Accumulation and softmax are fp32, out is
  * rounded to the pool dtype.  Page tables of different sequences may share
- * pages (shared prefixes, Sec. 3.4 fork_sequence); when neighbouring sequences
+ * pages (shared prefixes, Sec. 3.4; fork_sequence, Sec. 3.5); when neighbouring sequences
  * of the batch each bring one new token and their tables start with the same
  * pages (at least 512 tokens' worth, cached by all of them), the plan lets
  * them attend that prefix together, reading its K/V once, and merges the result
@@ -246,7 +265,7 @@ mc_status mc_prefix_prefill_attn_noalloc(const mc_pool_desc* pool, int32_t layer
 /* ---- transfer payload: pages <-> contiguous buffer -------------------------
  * (sender and receiver side of remote_send: KV of prompt[begin:end] goes to the
  * page/slot entries reserved by prep_recv, Sec. 3.1, Sec. 3.2 Example 2; a
- * layer's KV can go as soon as the layer is done, Sec. 3.5, hence layer-major.)
+ * layer's KV can go as soon as the layer is done, Sec. 3.6, hence layer-major.)
  * pages: device int32 table of ONE sequence, n_table_pages entries, must cover
  * token s1-1 (MC_ERR_RANGE otherwise).  Tokens [s0,s1), layers
  * [layer_begin, layer_end).  pack reads only those slots and writes only
@@ -259,8 +278,8 @@ mc_status mc_kv_unpack_range(const mc_pool_desc* pool, int32_t layer_begin, int3
                              const int32_t* pages /* device */, int32_t n_table_pages, int32_t s0,
                              int32_t s1, const void* sendbuf /* device */, void* stream);
 
-/* Batched form of the two calls above: one launch moves the ranges of `batch` sequences (an
- * engine serves several remote_send requests per layer, Sec. 3.5).  Sequence s owns table
+/* Batched form of the two calls above: one launch moves the ranges of `batch` sequences.
+ * Sequence s owns table
  * entries [cu_pages[s], cu_pages[s+1]) of page_table, tokens [s0[s], s1[s]) and the buffer
  * slice starting buf_offset[s] bytes into sendbuf (a multiple of 16; layout
  * [layer - layer_begin][2][token - s0[s]][kv_head][D] as above; slices must not overlap).
@@ -286,7 +305,7 @@ mc_status mc_kv_unpack_batch(const mc_pool_desc* pool, int32_t layer_begin, int3
                              int32_t max_range_pages, const void* sendbuf /* device */,
                              void* stream);
 
-/* ---- fork_sequence (Sec. 3.4) -------------------------------------------------
+/* ---- fork_sequence (Sec. 3.5) -------------------------------------------------
  * A new sequence that continues the first n_tokens tokens of a parent.  Its page
  * table lists the parent's whole pages (shared, read-only for both from now on:
  * attention and pack may read shared pages, Sec. 3.4) and, if n_tokens is not a
@@ -308,7 +327,7 @@ mc_status mc_kv_copy_page(const mc_pool_desc* pool, int32_t layer_begin, int32_t
                           int32_t src_page, int32_t dst_page, int32_t slots, void* stream);
 
 /* ---- host arithmetic of remote_send ------------------------------------------
- * Which token ranges a sender copies, computes and sends (Sec. 3.4, the two
+ * Which token ranges a sender copies, computes and sends (Sec. 3.5, the two
  * prefix-matching cases of the attention/transfer interface).  The sender's
  * cache holds prompt[0, sender_match), the receiver's prompt[0, receiver_match)
  * (what its prep_recv matched, Sec. 3.2); remote_send(begin, end) has to leave
@@ -342,8 +361,8 @@ mc_status mc_addr_expand(const int32_t* runs /* host [2 n_runs] */, int32_t n_ru
                          int32_t* pages_out /* host */, int32_t capacity, int32_t* n_out);
 
 /* ---- context cache index behind prep_recv ------------------------------------
- * prep_recv "checks for the existence of prompt[:end] in the KV cache" and
- * reports "the matched prefix length match_len" (Sec. 3.1, Sec. 3.2 Example 3).
+ * prep_recv looks the prompt up in the engine's context cache and reports how long
+ * a prefix of it is already there (match_len; Sec. 3.1, Sec. 3.2 Example 3).
  * The index records which page holds the KV of which 16-token block of which
  * token prefix: a trie over whole pages (a block is shared only if every token
  * before it is the same, and a partly filled last page is never shared, since

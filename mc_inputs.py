@@ -61,7 +61,7 @@ class Workload:
     page_tables: List[np.ndarray] = field(default_factory=list)  # per seq, ceil(n/P) page ids
     head_dim: int = 128
     page_size: int = 16
-    # shared prefixes (fork_sequence, paper Sec. 3.4): share[s] = (source sequence < s, tokens);
+    # shared prefixes (fork_sequence, paper Sec. 3.5): share[s] = (source sequence < s, tokens);
     # sequence s has the source's K/V on its first `tokens` tokens (a multiple of the page size)
     # and lists the source's pages for them
     share: dict = field(default_factory=dict)

@@ -224,7 +224,7 @@ class Allocator:
         return lib().orc_alloc_give(self._h, pages.size, _p(pages)) == 0
 
 
-# ---- host arithmetic of remote_send (paper Sec. 3.4, the two prefix-matching cases) ----
+# ---- host arithmetic of remote_send (paper Sec. 3.5, the two prefix-matching cases) ----
 def send_plan(sender_match: int, receiver_match: int, begin: int, end: int) -> dict:
     """Token by token.  Token t of the prompt is on the sender if t < sender_match and on the
     receiver if t < receiver_match.  The receiver needs t if begin <= t < end and it does not
@@ -288,7 +288,7 @@ def prep_recv(index: PrefixIndex, alloc: Allocator, prompt, end: int):
     return pages + fresh, match_len
 
 
-# ---- fork_sequence (paper Sec. 3.4) ----
+# ---- fork_sequence (paper Sec. 3.5) ----
 def fork_sequence(alloc: Allocator, parent_pages, n_tokens: int, page_size: int = 16):
     """The child's page list for the parent's first n_tokens tokens: whole pages shared, a fresh
     page for a partly filled last one; plus the copy to make as (src page, dst page, slots), or

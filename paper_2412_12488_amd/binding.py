@@ -16,7 +16,7 @@ EXPORTS = [
     "mc_status_string", "mc_abi_version",
     "mc_kv_allocator_create", "mc_kv_allocator_destroy", "mc_kv_alloc_pages", "mc_kv_free_pages",
     "mc_kv_allocator_num_free", "mc_kv_check_page_table",
-    "mc_kv_append", "mc_kv_append_send", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_ahead", "mc_attn_plan_check",
+    "mc_kv_copy_check", "mc_kv_append", "mc_kv_append_send", "mc_attn_workspace_size", "mc_attn_plan", "mc_attn_plan_ahead", "mc_attn_plan_check",
     "mc_prefix_prefill_attn", "mc_prefix_prefill_attn_noalloc", "mc_kv_pack_range", "mc_kv_unpack_range",
     "mc_kv_pack_batch", "mc_kv_unpack_batch",
     "mc_plan_remote_send", "mc_addr_compress", "mc_addr_expand",
@@ -39,7 +39,7 @@ class mc_send_plan(C.Structure):
 class mc_pool_desc(C.Structure):
     _fields_ = [("base", C.c_void_p), ("num_layers", C.c_int32), ("num_pages", C.c_int32),
                 ("page_size", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
-                ("dtype", C.c_int32)]
+                ("dtype", C.c_int32), ("skipped", C.c_void_p)]
 
 
 _lib = None
@@ -65,6 +65,7 @@ def lib():
     L.mc_kv_free_pages.argtypes = [vp, i32, C.POINTER(i32)]
     L.mc_kv_allocator_num_free.argtypes = [vp, C.POINTER(i32)]
     L.mc_kv_check_page_table.argtypes = [C.POINTER(i32), i64, i32]
+    L.mc_kv_copy_check.argtypes = [pd, C.POINTER(i32), vp]
     L.mc_kv_append.argtypes = [pd, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp]
     L.mc_kv_append_send.argtypes = [pd, i32, vp, vp, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp,
                                     vp]
@@ -135,8 +136,11 @@ def mc_abi_version() -> int:
     return lib().mc_abi_version()
 
 
-def pool_desc(base, num_layers, num_pages, num_kv_heads, dtype, page_size=16, head_dim=128):
-    return mc_pool_desc(_ptr(base), num_layers, num_pages, page_size, num_kv_heads, head_dim, dtype)
+def pool_desc(base, num_layers, num_pages, num_kv_heads, dtype, page_size=16, head_dim=128,
+              skipped=None):
+    """skipped: optional device int32 counter (zeroed by the caller) for mc_kv_copy_check."""
+    return mc_pool_desc(_ptr(base), num_layers, num_pages, page_size, num_kv_heads, head_dim, dtype,
+                        _ptr(skipped))
 
 
 # ---- allocator (host) ---------------------------------------------------------
@@ -172,6 +176,16 @@ def mc_kv_check_page_table(pages, num_pages: int) -> int:
 
 
 # ---- device calls -------------------------------------------------------------
+def mc_kv_copy_check(pool: mc_pool_desc, stream=None) -> int:
+    """Status code (MC_OK / MC_ERR_RANGE / ...) and the count, as (status, skipped); does not
+    raise on MC_ERR_RANGE, since the count is the point."""
+    n = C.c_int32(0)
+    st = lib().mc_kv_copy_check(C.byref(pool), C.byref(n), _stream(stream))
+    if st not in (MC_OK, MC_ERR_RANGE):
+        raise McError(st, "mc_kv_copy_check")
+    return st, n.value
+
+
 def mc_kv_append(pool: mc_pool_desc, layer, k_new, v_new, batch, total_q, cu_q, begin,
                  page_table, cu_pages, stream=None):
     _check(lib().mc_kv_append(C.byref(pool), layer, _ptr(k_new), _ptr(v_new), batch, total_q,

@@ -9,7 +9,7 @@
 //     tokens x G query heads of one kv head's group, TOK = 128/G, token-major) over
 //     a range of 64-key KV tiles - the whole range, or a chunk of it when the batch
 //     alone would not fill the GPU (decode steps, short ranges over long contexts),
-//     or the prefix that neighbouring decode rows share (fork_sequence, Sec. 3.4).
+//     or the prefix that neighbouring decode rows share (Sec. 3.4; fork_sequence, Sec. 3.5).
 //     Items are ordered longest first.
 //   * attn_kernel: one workgroup (4 wavefronts of 64) per (item, kv head), so every
 //     K/V byte staged in LDS serves the whole GQA group.  Items that cover a whole
@@ -75,9 +75,10 @@ static_assert(sizeof(PlanHeader) == 64, "header is 64 bytes");
 // part < 0: the item covers the tile's whole KV range and writes out/lse itself.  Otherwise it
 // writes a partial result (O normalised within the chunk, fp32, and the chunk's LSE) for token
 // tt of the tile at row part + tt of the partial arrays, and merge_kernel combines the chunks.
-// gsize > 0: a shared-prefix item.  Its rows are the single new tokens of gsize consecutive
-// sequences starting at seq, whose page tables begin with the same pages; it covers tiles of
-// that common prefix (all of it visible to every row) and always writes partial rows.
+// gsize > 0: a shared-prefix item.  Its rows are the gsize new tokens of consecutive sequences
+// starting at seq (neighbours in the q array: tokens cu_q[seq] .. cu_q[seq] + gsize - 1), whose
+// page tables begin with the same pages; it covers tiles of that common prefix (all of it
+// visible to every row) and always writes partial rows.
 struct ItemRec {
   int32_t seq, row0, t0, t1, part, gsize, pad[2];
 };
@@ -85,7 +86,7 @@ static_assert(sizeof(ItemRec) == 32, "item record is 32 bytes");
 
 // One q tile with partial results: chunk c of its own KV range has its partial rows at
 // part + c * ntok; if the tile's sequence belongs to a shared-prefix group, chunk c of the
-// prefix has this sequence's row at g_part + c * g_stride.
+// prefix has this sequence's rows from g_part + c * g_stride on (g_stride = the group's tokens).
 struct MergeRec {
   int32_t q_row;   // index of the tile's first token among all new tokens of the batch
   int32_t ntok, nsplit, part;
@@ -366,10 +367,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     return;
   }
 
-  // 3b. shared-prefix groups (Sec. 3.4 fork_sequence: sequences may share the pages of a common
-  //     prefix).  Decode rows of neighbouring sequences whose tables start with the same pages
-  //     attend that prefix together, one K/V read for all of them, and their own remainders one
-  //     by one; the parts are merged by LSE like any other chunks.
+  // 3b. shared-prefix groups (Sec. 3.4, fork_sequence in Sec. 3.5: sequences may share the pages of a common
+  //     prefix).  The new tokens of neighbouring sequences with short new ranges (decode rows,
+  //     or a few tokens each) whose tables start with the same pages attend that prefix together
+  //     as one q tile - their tokens are neighbours in the q array, and every key of the prefix
+  //     lies before every one of them, so no mask is involved - one K/V read for all of them,
+  //     and their own remainders one by one; the parts are merged by LSE like any other chunks.
   const bool try_groups = a.allow_groups && cu_in_lds && a.batch >= 2;
   if (t == 0) s_groups = 0;
   if (try_groups) {
@@ -379,7 +382,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     // pair at once, one thread each: unrelated sequences differ in their first page and are
     // done (s_common = 1 marks a pair that is not).  Then one wavefront a remaining pair.
     constexpr int kMinPages = kMinSharedTiles * kBN / kPage;
-    if (t + 1 < a.batch && s_cuq[t + 1] - s_cuq[t] == 1 && s_cuq[t + 2] - s_cuq[t + 1] == 1 &&
+    // a sequence can be a member if its new range leaves room for another token in a q tile
+    auto is_short = [&](int sq) {
+      const int q = s_cuq[sq + 1] - s_cuq[sq];
+      return q >= 1 && q < a.tile_tokens;
+    };
+    if (t + 1 < a.batch && is_short(t) && is_short(t + 1) &&
         min(s_beg[t], s_beg[t + 1]) / kPage >= kMinPages &&
         a.page_table[s_cup[t]] == a.page_table[s_cup[t + 1]])
       s_common[t] = 1;
@@ -399,32 +407,44 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       if ((t & 63) == 0) s_common[sq] = common;
     }
     __syncthreads();
-    // runs of decode rows linked by enough common pages, cut into groups of at most tile_tokens
+    // runs of such sequences linked by enough common pages, cut into groups of at most
+    // tile_tokens new tokens: the thread of a run's first sequence walks the run
     const bool mine = t < a.batch;
-    const bool dec = mine && s_cuq[t + 1] - s_cuq[t] == 1;
     auto linked = [&](int sq) {   // sq and sq+1 sit in one run
-      return sq >= 0 && sq + 1 < a.batch && s_cuq[sq + 1] - s_cuq[sq] == 1 &&
-             s_cuq[sq + 2] - s_cuq[sq + 1] == 1 && s_common[sq] >= kMinPages;
+      return sq >= 0 && sq + 1 < a.batch && is_short(sq) && is_short(sq + 1) &&
+             s_common[sq] >= kMinPages;
     };
-    const bool starts = dec && !linked(t - 1);
-    const int run_start = block_inclusive_max_scan(starts ? t : -1, scan);
-    int lead = -1;
-    if (dec && run_start >= 0) {
-      lead = run_start + (t - run_start) / a.tile_tokens * a.tile_tokens;
-      if (t == lead) {
-        int m = 1, pages = INT32_MAX;
-        while (m < a.tile_tokens && linked(t + m - 1)) { pages = min(pages, s_common[t + m - 1]); ++m; }
-        if (m >= 2) {
-          s_gsize[t] = m;
-          s_gbase[t] = (pages / (2 * kBN / kPage)) * 2;   // prefix tiles, even (scratch until step 5)
+    if (mine && is_short(t) && !linked(t - 1) && linked(t)) {
+      int lead = t, tokens = 0, members = 0, pages = INT32_MAX;
+      auto close_group = [&]() {
+        if (members >= 2) {
+          s_gsize[lead] = tokens;                          // rows of the group's q tile
+          s_gbase[lead] = (pages / (2 * kBN / kPage)) * 2; // prefix tiles, even (scratch until step 5)
+          s_groups = 1;
+        } else {
+          s_glead[lead] = -1;
         }
+      };
+      for (int sq = t;; ++sq) {
+        const int q = s_cuq[sq + 1] - s_cuq[sq];
+        if (tokens + q > a.tile_tokens) {                  // the tile is full: next group
+          close_group();
+          lead = sq; tokens = 0; members = 0; pages = INT32_MAX;
+        }
+        if (members > 0) pages = min(pages, s_common[sq - 1]);
+        s_glead[sq] = lead;
+        tokens += q;
+        ++members;
+        if (!linked(sq)) break;
       }
+      close_group();
     }
     __syncthreads();
-    if (dec && lead >= 0 && s_gsize[lead] >= 2 && t - lead < s_gsize[lead]) {
-      s_gp[t] = s_gbase[lead];
-      s_glead[t] = lead;
-      s_groups = 1;
+    // every member learns the prefix its group covers (a lead without a group has none)
+    if (mine) {
+      const int lead = s_glead[t];
+      if (lead >= 0 && s_gsize[lead] > 0) s_gp[t] = s_gbase[lead];
+      else s_glead[t] = -1;
     }
     __syncthreads();
   }
@@ -432,7 +452,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
 
   // q tile i: its sequence, first row, token count, KV tiles, the last even tile index at which
   // a chunk may start (every row must see at least the first key of every chunk), the prefix
-  // tiles its shared-prefix group covers, and the group's size if this tile leads one
+  // tiles its shared-prefix group covers, and the group's new tokens if this tile leads one
   struct Tile { int s, row0, ntok, T, dmax, pt, gm; };
   auto locate = [&](int i) {
     int lo = 0, hi = a.batch;
@@ -596,7 +616,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       m.nsplit = ns;
       m.part = own_off;
       m.g_nsplit = ng;
-      m.g_part = x.pt > 0 ? s_gbase[s_glead[x.s]] + (x.s - s_glead[x.s]) : 0;
+      m.g_part = x.pt > 0 ? s_gbase[s_glead[x.s]] + (s_cuq[x.s] - s_cuq[s_glead[x.s]]) : 0;
       m.g_stride = x.pt > 0 ? s_gsize[s_glead[x.s]] : 0;
       m.tok_off = mtok_off;
       mtok_off += x.ntok;
@@ -796,9 +816,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const int gsize = item[5];                         // > 0: shared-prefix item over gsize sequences
   // a record that cannot come from the planner (a workspace written over by something else)
   if ((unsigned)seq >= (unsigned)a.batch || row0 < 0 || t0 < 0 || item[3] <= t0 || gsize < 0 ||
-      gsize > TOK || seq + max(gsize, 1) > a.batch)
+      gsize > TOK)
     return;
   const int q0 = a.cu_q[seq], q_len = a.cu_q[seq + 1] - q0, b = a.begin[seq];
+  if (q0 < 0 || (int64_t)q0 + gsize > a.total_q) return;   // a group's rows are tokens of the q array
   // valid tokens in this tile (>= 1), and the position of the first one.  The rows of a
   // shared-prefix item are the new tokens of gsize consecutive sequences; all of them lie
   // beyond the prefix, so any position at or past the item's last key serves.
@@ -815,7 +836,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   // the range - ends the workgroup before any table entry is read; table indices never leave
   // the sequence's own slice of the page table
   const int table_len = a.cu_pages[seq + 1] - a.cu_pages[seq];
-  if (b < 0 || ntok <= 0 || kv_len <= kBN * t0 || table_len <= 0) return;
+  if (b < 0 || ntok <= 0 || kv_len <= kBN * t0 || table_len <= 0) {
+    // a chunk that is not computed says so in its partial rows (no key seen: LSE = -inf), so
+    // that the merge gives it no weight, and writes nothing if no chunk of the row was computed
+    if (part >= 0 && ntok > 0)
+      for (int i = tid; i < ntok * G; i += kThreads)
+        a.part_lse[(int64_t)(part + i / G) * a.hq + hk * G + i % G] = -INFINITY;
+    return;
+  }
   const int last_pidx = min((kv_len - 1) / kPage, table_len - 1);   // last entry that holds a needed key
   const_i32_ptr table = (const_i32_ptr)(a.page_table + a.cu_pages[seq]);
 
@@ -860,21 +888,37 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   auto copy_page = [&](const char* base, bool is_v, uint32_t lds_page) __attribute__((always_inline)) {   // 16 rows = 4 KiB
     copy16_to_lds(base, is_v ? v_lane_off : k_lane_off, lds_page + wave * 1024);
   };
+  // ---- the page-id register -----------------------------------------------------------
   // The page ids of a tile's copies are fetched one tile early by a vector load (lane i & 7
-  // holds table entry first + i) issued, like the copies, outside the compiler's wait
-  // tracking, and moved to scalar registers when the addresses are built.
+  // holds table entry first + i) that is issued, like the copies, as an assembly statement: the
+  // compiler does not count it and places no wait for it.  Everything that touches the register
+  // is in this struct, and the three steps have one legal order:
+  //   issue(first)  the load is in flight; the register must not be read
+  //   arrive()      s_waitcnt vmcnt(0), with the register as an in/out operand of the statement:
+  //                 every later read depends on it and cannot be scheduled above the wait (the
+  //                 same wait covers the tile's global -> LDS copies, hence the barrier after it)
+  //   value()       the ids; only between an arrive() and the next issue()
+  // A register copy of `reg` made between issue() and arrive() would read a stale value: there
+  // is none, because nothing outside these methods names it.
   const int32_t* table_g = a.page_table + a.cu_pages[seq];
-  auto fetch_ids = [&](int first) __attribute__((always_inline)) {
-    const int32_t* p = table_g + min(first + (lane & 7), last_pidx);
-    int32_t v;
-    asm volatile("global_load_dword %0, %1, off" : "=v"(v) : "v"(p) : "memory");
-    return v;
-  };
-  // The wait names ids_next as an operand: the register is written by a load the compiler does
-  // not track, so every later read of it must be ordered after this wait by data dependence.
-  int32_t ids_next;                       // table entries 4j+4 .. 4j+11 during tile j
+  struct PageIds {
+    int32_t reg;
+    const int32_t* table;
+    int lane7, last;
+    __device__ __forceinline__ void issue(int first) {
+      const int32_t* p = table + min(first + lane7, last);
+      asm volatile("global_load_dword %0, %1, off" : "=v"(reg) : "v"(p) : "memory");
+    }
+    __device__ __forceinline__ void arrive() {
+      asm volatile("s_waitcnt vmcnt(0)" : "+v"(reg) : : "memory");
+    }
+    __device__ __forceinline__ int32_t value() const { return reg; }
+  } ids;                                  // table entries 4j+4 .. 4j+11 during tile j
+  ids.table = table_g;
+  ids.lane7 = lane & 7;
+  ids.last = last_pidx;
   auto wait_copies_and_sync = [&]() __attribute__((always_inline)) {
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(ids_next) : : "memory");
+    ids.arrive();
     __syncthreads();
   };
 
@@ -1013,7 +1057,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const uint32_t page_stride_b = page_blocks << 12;
   struct TilePages { const char* pb[6]; };
   auto tile_pages = [&](int jt) __attribute__((always_inline)) {
-    const int32_t pg = min(max(ids_next, 0), a.num_pages - 1);   // checked by the plan; stay in bounds anyway
+    const int32_t pg = min(max(ids.value(), 0), a.num_pages - 1);   // checked by the plan; stay in bounds anyway
     const uint64_t addr = pool_k_u + (uint64_t)(uint32_t)pg * page_stride_b;
     const uint32_t lo = (uint32_t)addr, hi = (uint32_t)(addr >> 32);
     TilePages tp;
@@ -1021,7 +1065,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     for (int i = 0; i < 6; ++i)
       tp.pb[i] = (const char*)(size_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane(hi, i) << 32) |
                                        (uint32_t)__builtin_amdgcn_readlane(lo, i));
-    ids_next = fetch_ids(4 * jt + 8);
+    ids.issue(4 * jt + 8);
     return tp;
   };
   // copy c of the tile's eight: the pages of K half 2j+3, the first two of V(j+1), K half 2j+4,
@@ -1092,7 +1136,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) copy_page(pb[i], true, lds_v + i * 4096);
     }
-    ids_next = fetch_ids(4 * t0 + 4);
+    ids.issue(4 * t0 + 4);
     wait_copies_and_sync();
     if (wave_active) {
 #pragma unroll
@@ -1260,12 +1304,13 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     if (tt < 0 || tt >= m.ntok || h >= a.hq) continue;
     // partial row of chunk c: the shared prefix's chunks first, then the tile's own
     auto row_of = [&](int c) {
-      return (int64_t)(c < m.g_nsplit ? m.g_part + c * m.g_stride
+      return (int64_t)(c < m.g_nsplit ? m.g_part + c * m.g_stride + tt
                                       : m.part + (c - m.g_nsplit) * m.ntok + tt) * a.hq + h;
     };
     const int nchunks = m.g_nsplit + m.nsplit;
     float mx = -INFINITY;
     for (int c = 0; c < nchunks; ++c) mx = fmaxf(mx, a.part_lse[row_of(c)]);
+    if (!(mx > -INFINITY)) continue;   // no chunk of this row was computed: nothing to write
     float den = 0.f;
     f32x2 acc = {0.f, 0.f};
 #pragma unroll 4

@@ -18,6 +18,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline mc_status check_pool(const mc_pool_desc* pool) {
   if (!pool || !pool->base) return MC_ERR_INVALID;
   if (!aligned16(pool->base)) return MC_ERR_INVALID;
+  if (reinterpret_cast<uintptr_t>(pool->skipped) & 3u) return MC_ERR_INVALID;
   if (pool->num_layers <= 0 || pool->num_pages <= 0 || pool->num_kv_heads <= 0)
     return MC_ERR_INVALID;
   if (pool->page_size != kPage || pool->head_dim != kHeadDim) return MC_ERR_UNSUPPORTED;

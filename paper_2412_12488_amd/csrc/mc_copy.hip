@@ -1,6 +1,6 @@
 // Bandwidth-bound page copies for gfx950: KV append, and the page-range
 // gather/scatter behind remote_send / prep_recv (paper Sec. 3.1, Sec. 3.2
-// Example 2, Sec. 3.5).  No arithmetic: every lane moves 16 bytes at a time.
+// Example 2, Sec. 3.6).  No arithmetic: every lane moves 16 bytes at a time.
 //
 // Geometry (D = 128, P = 16, 2-byte elements): a (token, head) row is 256 B =
 // 16 lanes x 16 B; a (page, K|V, head) block is 16 rows = 4 KiB contiguous in the
@@ -37,7 +37,13 @@ struct RangeArgs {
   const int32_t* s0_of;
   const int32_t* s1_of;
   const int64_t* buf_offset;
+  int32_t* skipped;       // optional counter of what was left out for being out of bounds
 };
+
+// One lane of the workgroup reports a unit (page, sequence, token) left out as out of bounds.
+__device__ __forceinline__ void report_skip(int32_t* counter, bool this_lane) {
+  if (counter && this_lane) atomicAdd(counter, 1);
+}
 
 // grid.x: 2 * (page index within [s0/16, ceil(s1/16))) + (0 = K, 1 = V); grid.y: layer - layer_begin
 template <bool kPack, bool kBatched>
@@ -49,7 +55,12 @@ __global__ __launch_bounds__(kThreads) void range_copy_kernel(RangeArgs a) {
     a.s0 = a.s0_of[sq];
     a.s1 = a.s1_of[sq];
     const int64_t off = a.buf_offset[sq];
-    if (p0 < 0 || p1 < p0 || a.s0 < 0 || a.s1 <= a.s0 || off < 0 || (off & 15)) return;
+    if (a.s1 <= a.s0 && a.s0 >= 0) return;   // empty by its own statement
+    if (p0 < 0 || p1 < p0 || a.s0 < 0 || off < 0 || (off & 15)) {
+      // malformed sequence: counted once (by the workgroup of its first page, K, first layer)
+      report_skip(a.skipped, blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0);
+      return;
+    }
     a.pages += p0;
     a.n_table_pages = p1 - p0;
     a.buf += off;
@@ -61,9 +72,11 @@ __global__ __launch_bounds__(kThreads) void range_copy_kernel(RangeArgs a) {
   const int lk = blockIdx.y * 2 + (blockIdx.x & 1);
   const int slot = threadIdx.x >> 4, lane16 = threadIdx.x & 15;
   const int tok = tp * kPage + slot;
-  if (tp >= a.n_table_pages) return;
+  // a page the table does not hold or the pool does not have: counted once (K, first layer)
+  const bool reporter = (blockIdx.x & 1) == 0 && blockIdx.y == 0 && threadIdx.x == 0;
+  if (tp >= a.n_table_pages) { report_skip(a.skipped, reporter); return; }
   const int32_t page = a.pages[tp];
-  if (page < 0 || page >= a.num_pages) return;
+  if (page < 0 || page >= a.num_pages) { report_skip(a.skipped, reporter); return; }
   const bool live = tok >= a.s0 && tok < a.s1;
   const int layer = a.layer_begin + (lk >> 1), kv = lk & 1;
   const int64_t T = a.s1 - a.s0;
@@ -110,6 +123,7 @@ struct AppendArgs {
   const int32_t* s1_of;
   const int64_t* buf_offset;
   int32_t layer_rel;       // layer - first layer of the transfer buffer
+  int32_t* skipped;        // optional counter of tokens left out for being out of bounds
 };
 
 // grid.x: 2 * (chunk of 16 consecutive tokens of the ragged new-token stream) + (0 = K, 1 = V)
@@ -127,14 +141,15 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a) {
   }
   const int s = lo;
   const int q0 = a.cu_q[s];
-  if (g < q0 || g >= a.cu_q[s + 1]) return;          // malformed offsets: skip
+  const bool reporter = kv == 0 && lane16 == 0;      // one lane per token
+  if (g < q0 || g >= a.cu_q[s + 1]) { report_skip(a.skipped, reporter); return; }   // malformed offsets
   const int pos = a.begin[s] + (g - q0);
-  if (pos < 0) return;
+  if (pos < 0) { report_skip(a.skipped, reporter); return; }
   const int p0 = a.cu_pages[s], p1 = a.cu_pages[s + 1];
   const int tp = pos / kPage;
-  if (p0 < 0 || tp >= p1 - p0) return;               // table too short: skip
+  if (p0 < 0 || tp >= p1 - p0) { report_skip(a.skipped, reporter); return; }       // table too short
   const int32_t page = a.page_table[p0 + tp];
-  if (page < 0 || page >= a.num_pages) return;
+  if (page < 0 || page >= a.num_pages) { report_skip(a.skipped, reporter); return; }
   const char* src = (kv ? a.v_new : a.k_new) + (int64_t)g * a.hkv * kRowBytes + lane16 * 16;
   char* dst = a.pool_layer + page * a.page_stride + (int64_t)kv * a.hkv * kHeadPageBytes +
               (pos % kPage) * kRowBytes + lane16 * 16;
@@ -217,6 +232,7 @@ mc_status range_copy(bool pack, const mc_pool_desc* pool, int32_t layer_begin, i
   a.s0_of = nullptr;
   a.s1_of = nullptr;
   a.buf_offset = nullptr;
+  a.skipped = pool->skipped;
   const int first = s0 / kPage, last = (s1 - 1) / kPage;
   dim3 grid(2u * (last - first + 1), (unsigned)gy);
   hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -259,6 +275,7 @@ mc_status range_copy_batch(bool pack, const mc_pool_desc* pool, int32_t layer_be
   a.s0_of = s0;
   a.s1_of = s1;
   a.buf_offset = buf_offset;
+  a.skipped = pool->skipped;
   dim3 grid(2u * (unsigned)max_range_pages, (unsigned)gy, (unsigned)batch);
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (pack)
@@ -337,6 +354,7 @@ static mc_status append_impl(const mc_pool_desc* pool, int32_t layer, const void
   a.s1_of = s1;
   a.buf_offset = buf_offset;
   a.layer_rel = send ? layer - send_layer_begin : 0;
+  a.skipped = pool->skipped;
   dim3 grid(2u * ((total_q + kPage - 1) / kPage));
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (send)
@@ -362,6 +380,19 @@ mc_status mc_kv_append_send(const mc_pool_desc* pool, int32_t layer, const void*
                             void* stream) {
   return append_impl(pool, layer, k_new, v_new, batch, total_q, cu_q, begin, page_table, cu_pages,
                      true, send_layer_begin, s0, s1, buf_offset, sendbuf, stream);
+}
+
+mc_status mc_kv_copy_check(const mc_pool_desc* pool, int32_t* skipped_out, void* stream) {
+  if (!pool || !pool->skipped || (reinterpret_cast<uintptr_t>(pool->skipped) & 3u))
+    return MC_ERR_INVALID;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  int32_t n = 0;
+  if (hipMemcpyAsync(&n, pool->skipped, sizeof(n), hipMemcpyDeviceToHost, hs) != hipSuccess ||
+      hipMemsetAsync(pool->skipped, 0, sizeof(n), hs) != hipSuccess ||
+      hipStreamSynchronize(hs) != hipSuccess)
+    return MC_ERR_HIP;
+  if (skipped_out) *skipped_out = n;
+  return n == 0 ? MC_OK : MC_ERR_RANGE;
 }
 
 mc_status mc_kv_copy_page(const mc_pool_desc* pool, int32_t layer_begin, int32_t layer_end,

@@ -1,6 +1,6 @@
 // Host-only parts of the library: status names, the page allocator behind
-// prep_recv (paper Sec. 3.1: "allocates KV cache entries for the missing
-// subsequence"), and a host check of destination page tables.
+// prep_recv (paper Sec. 3.1: the receiver reserves entries for the part of the prompt it
+// does not hold), and a host check of destination page tables.
 #include <algorithm>
 #include <array>
 #include <map>
@@ -60,7 +60,7 @@ const char* mc_status_string(int32_t status) {
   }
 }
 
-int32_t mc_abi_version(void) { return 1; }
+int32_t mc_abi_version(void) { return 2; }
 
 mc_status mc_kv_allocator_create(int32_t num_pages, void** alloc_out) {
   if (!alloc_out || num_pages < 0) return MC_ERR_INVALID;

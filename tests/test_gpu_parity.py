@@ -55,6 +55,54 @@ def test_append_bytes(case):
     assert not np.array_equal(opool, init)
 
 
+def test_copies_report_what_they_skip():
+    """Tokens and pages a copy kernel leaves out because a table index or a page id is out of
+    bounds are counted (mc_kv_copy_check); well-formed calls count nothing, and what is left out
+    is neither read nor written."""
+    w = small_workload(106, mi.BF16, 8, 8, [45, 100, 33], [13, 0, 32], layers=2)
+    init = canary(12, DevPool(w).elems)
+    counter = torch.zeros(1, dtype=torch.int32, device=DEV)
+    pool = DevPool(w, fill=init)
+    pool.desc = mc.pool_desc(pool.t, 2, w.num_pages, 8, w.dtype, skipped=counter)
+    db = DevBatch(w)
+    k = dev(np.concatenate([w.kv(s, 1)[0][w.b[s]:] for s in range(3)]))
+    v = dev(np.concatenate([w.kv(s, 1)[1][w.b[s]:] for s in range(3)]))
+    gpu_append(pool, 1, k, v, db)
+    assert mc.mc_kv_copy_check(pool.desc) == (mc.MC_OK, 0)
+    # a page id outside the pool in sequence 1 (tokens 16..31) and a table one entry too short
+    # for sequence 2 (its token 32 has no page): 16 + 1 tokens are left out
+    good = bits(pool.t).copy()
+    pool.t.copy_(dev(init))
+    table = w.flat_page_table.copy()
+    table[int(w.cu_pages[1]) + 1] = w.num_pages + 3
+    cu_pages = w.cu_pages.copy()
+    cu_pages[3] -= 1
+    mc.mc_kv_append(pool.desc, 1, k, v, 3, db.total_q, db.cu_q, db.begin, dev(table), dev(cu_pages))
+    assert mc.mc_kv_copy_check(pool.desc) == (mc.MC_ERR_RANGE, 17)
+    assert mc.mc_kv_copy_check(pool.desc) == (mc.MC_OK, 0)          # the check set it back to zero
+    got = bits(pool.t)
+    shape5 = (2, w.num_pages, 2, 8, 16, 128)
+    g5, ok5, i5 = got.reshape(shape5), good.reshape(shape5), init.reshape(shape5)
+    bad_page, short_page = int(w.page_tables[1][1]), int(w.page_tables[2][2])
+    for page in range(w.num_pages):          # skipped tokens leave their slots as they were
+        ref = i5 if page in (bad_page, short_page) else ok5
+        assert np.array_equal(g5[:, page], ref[:, page]), page
+    # pack with the bad table: the page is counted once, its slice of the buffer stays untouched
+    send = dev(canary(13, 2 * 2 * 100 * 8 * 128))
+    before = bits(send).copy()
+    mc.mc_kv_pack_range(pool.desc, 0, 2, dev(table[w.cu_pages[1]:w.cu_pages[2]]), 7, 0, 100, send)
+    assert mc.mc_kv_copy_check(pool.desc) == (mc.MC_ERR_RANGE, 1)
+    after = bits(send).reshape(2, 2, 100, 8 * 128)
+    assert np.array_equal(after[:, :, 16:32], before.reshape(2, 2, 100, 8 * 128)[:, :, 16:32])
+    assert not np.array_equal(after[:, :, :16], before.reshape(2, 2, 100, 8 * 128)[:, :, :16])
+    # batched unpack: a sequence with a misaligned buffer offset is left out and counted once;
+    # an empty range is not counted
+    s0, s1 = dev(np.array([0, 0, 5], np.int32)), dev(np.array([45, 100, 5], np.int32))
+    off = torch.tensor([0, 8, 0], dtype=torch.int64, device=DEV)
+    mc.mc_kv_unpack_batch(pool.desc, 0, 1, 3, db.page_table, db.cu_pages, s0, s1, off, 7, send)
+    assert mc.mc_kv_copy_check(pool.desc) == (mc.MC_ERR_RANGE, 1)
+
+
 def test_append_nothing_is_a_no_op():
     w = small_workload(102, mi.BF16, 8, 8, [32], [32])
     init = canary(2, DevPool(w).elems)
@@ -334,7 +382,7 @@ def plan_header(w):
     mc.mc_attn_plan_check(ws)
     h = ws[:64].view(torch.int32).cpu().numpy()
     return {"num_items": int(h[2]), "tile_tokens": int(h[3]), "num_merges": int(h[6]),
-            "chunk_tiles": int(h[7])}
+            "chunk_tiles": int(h[7]), "num_groups_rows": int(h[8])}
 
 
 @pytest.mark.parametrize("Hq,Hkv,dtype", [(32, 8, mi.BF16), (8, 8, mi.F16), (64, 8, mi.BF16)])
@@ -396,7 +444,7 @@ def forked_decode_workload(seed, Hq, Hkv, dtype, groups, extra=()):
 
 @pytest.mark.parametrize("Hq,Hkv,dtype", [(32, 8, mi.BF16), (8, 8, mi.F16)])
 def test_decode_rows_sharing_a_prefix(Hq, Hkv, dtype):
-    # forks of a common prompt (Sec. 3.4 fork_sequence): their page tables start with the same
+    # forks of a common prompt (Sec. 3.5 fork_sequence): their page tables start with the same
     # pages.  Neighbouring decode rows attend the shared prefix together and their own
     # remainders alone; results must equal plain per-sequence attention.
     groups = [
@@ -414,6 +462,29 @@ def test_decode_rows_sharing_a_prefix(Hq, Hkv, dtype):
     mc.mc_attn_plan_check(ws)
     h = ws[:64].view(torch.int32).cpu().numpy()
     assert int(h[8]) > 0, h[:9]          # shared-prefix items were planned
+    check_attention(w)
+
+
+@pytest.mark.parametrize("dtype", [mi.BF16, mi.F16])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (32, 8), (64, 8)])
+def test_short_ranges_sharing_a_prefix(dtype, Hq, Hkv):
+    """Forks of one 2048-token prompt that each bring a few new tokens (3..40), after own middle
+    parts of different lengths: those whose new tokens fit a q tile together attend the shared
+    prefix as one tile; an unrelated sequence in between ends a run.  Every row vs the oracle."""
+    rng = mi.rng_for(760 + Hq)
+    new = [int(x) for x in rng.integers(3, 15, size=9)]
+    new[7] = 40                                        # too long for a shared tile of 32 tokens
+    own = [int(x) for x in rng.integers(0, 200, size=9)]
+    begins = [2048 + o for o in own]
+    begins[4] = 700                                    # sequence 4 is not a fork
+    lens = [b + q for b, q in zip(begins, new)]
+    w = small_workload(761, dtype, Hq, Hkv, lens, begins)
+    for s in range(1, 9):
+        if s != 4:
+            w.share_prefix(s, 0, 2048)
+    h = plan_header(w)
+    if 128 // (Hq // Hkv) > 16:                        # tiles of 16 tokens hold few of these ranges
+        assert h["num_groups_rows"] > 0, h
     check_attention(w)
 
 
@@ -496,7 +567,7 @@ def test_decode_step_under_graph_capture():
 def test_remote_send_flow_for_the_prefix_matching_cases(sender_cached, receiver_cached):
     """prep_recv on the receiver, remote_send on the sender (copy what is cached, prefill the
     rest, send what the receiver lacks), start_generate on the receiver (Sec. 3.1, Sec. 3.2,
-    Sec. 3.4 cases 1 and 2): afterwards the receiver holds exactly the prompt's KV and its
+    Sec. 3.5 cases 1 and 2): afterwards the receiver holds exactly the prompt's KV and its
     last-token attention equals the oracle's."""
     Hq, Hkv, n, pages_total = 32, 8, 400, 64
     end = n - 1                                             # the receiver prefills the last token
@@ -690,7 +761,7 @@ def test_append_send_writes_pool_and_marked_rows():
 
 
 def test_fork_sequence_copies_the_partial_page_and_forks_diverge():
-    """fork_sequence (Sec. 3.4): the child shares the parent's whole pages and gets a copy of the
+    """fork_sequence (Sec. 3.5): the child shares the parent's whole pages and gets a copy of the
     partly filled one; both then append their own next token and attend: each sees the common
     100 tokens and only its own new one."""
     Hq, Hkv, L, n = 32, 8, 2, 100
@@ -796,6 +867,100 @@ def test_one_plan_for_many_decode_steps():
     with pytest.raises(mc.McError) as e:
         mc.mc_attn_plan_check(ws)
     assert e.value.status == mc.MC_ERR_RANGE
+
+
+def test_one_plan_with_forks_and_a_prefill_range_up_to_a_tile_edge():
+    """mc_attn_plan_ahead over a batch that holds a group of forks (their shared prefix is
+    attended together; the group's items keep their KV range while the members' own remainders
+    grow), an unrelated decode row and a prefill range: every begin grows step by step until it
+    has grown by exactly ahead_tokens, where the first fork's keys end on a 64-key tile edge.
+    Every row is checked against the oracle at every step."""
+    ahead, Hq, Hkv = 23, 32, 8
+    start = [1000, 1300, 1040, 777, 300]                 # lengths before the first step
+    qlen = [1, 1, 1, 1, 40]                              # new tokens per step
+    assert (start[0] + ahead + 1) % 64 == 0
+    final = [n + ahead + q for n, q in zip(start, qlen)]
+    w_full = small_workload(725, mi.BF16, Hq, Hkv, final, [0] * 5)
+    w_full.share_prefix(1, 0, 960)                       # forks of sequence 0: 60 shared pages
+    w_full.share_prefix(2, 0, 960)
+    B = 5
+    pool = DevPool(w_full)
+    opool = oracle.new_pool(pool.shape)
+    kv = [w_full.kv(s) for s in range(B)]
+    w0 = w_full.with_ranges(np.zeros(B, dtype=np.int64), np.array(start))
+    gpu_append(pool, 0, dev(np.concatenate([kv[s][0][:start[s]] for s in range(B)])),
+               dev(np.concatenate([kv[s][1][:start[s]] for s in range(B)])), DevBatch(w0))
+    for s in range(B):
+        oracle.append(opool, pool.shape, 0, kv[s][0][:start[s]], kv[s][1][:start[s]], 0,
+                      w_full.page_tables[s])
+    w_step = w_full.with_ranges(np.array(start), np.array(start) + np.array(qlen))
+    db = DevBatch(w_step)
+    tq = int(sum(qlen))
+    ws_bytes = mc.mc_attn_workspace_size(B, tq, Hq, Hkv)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    mc.mc_attn_plan_ahead(pool.desc, Hq, B, tq, db.cu_q, db.begin, db.page_table, db.cu_pages, ahead,
+                          ws, ws_bytes)
+    mc.mc_attn_plan_check(ws)
+    hdr = ws[:64].view(torch.int32).cpu().numpy()
+    assert hdr[8] > 0, hdr                               # partial rows of a shared-prefix group
+    out = torch.zeros((tq, Hq, 128), dtype=torch.int16, device=DEV)
+    lse = torch.zeros((tq, Hq), dtype=torch.float32, device=DEV)
+    # one query row per position of every sequence
+    q_all = [mi.normal_bits(mi.rng_for(725, s, mi.KIND_Q), (final[s], Hq, 128), mi.BF16) for s in range(B)]
+    for t in range(ahead + 1):
+        pos = [n + t for n in start]
+        begin = dev(np.array(pos, dtype=np.int32))
+        k_new = np.concatenate([kv[s][0][pos[s]:pos[s] + qlen[s]] for s in range(B)])
+        v_new = np.concatenate([kv[s][1][pos[s]:pos[s] + qlen[s]] for s in range(B)])
+        q = np.concatenate([q_all[s][pos[s]:pos[s] + qlen[s]] for s in range(B)])
+        mc.mc_kv_append(pool.desc, 0, dev(k_new), dev(v_new), B, tq, db.cu_q, begin, db.page_table,
+                        db.cu_pages)
+        mc.mc_prefix_prefill_attn(pool.desc, 0, dev(q), Hq, B, tq, db.cu_q, begin, db.page_table,
+                                  db.cu_pages, 0.0, out, lse, ws, ws_bytes)
+        torch.cuda.synchronize()
+        lo = 0
+        for s in range(B):
+            oracle.append(opool, pool.shape, 0, k_new[lo:lo + qlen[s]], v_new[lo:lo + qlen[s]], pos[s],
+                          w_full.page_tables[s])
+            ro, rl = oracle.attention(opool, pool.shape, 0, w_full.page_tables[s], q[lo:lo + qlen[s]],
+                                      Hq, pos[s], pos[s] + qlen[s])
+            go = oracle.decode(bits(out[lo:lo + qlen[s]]), mi.BF16)
+            assert np.max(np.abs(go - ro)) <= O_TOL, (t, s)
+            assert np.max(np.abs(lse[lo:lo + qlen[s]].cpu().numpy() - rl)) <= LSE_TOL, (t, s)
+            lo += qlen[s]
+
+
+def test_a_begin_that_no_longer_fits_the_plan_writes_nothing():
+    """The attention call reads begin itself.  A value the plan was not made for - negative, or
+    far below the planned one - must neither fault nor read outside the sequence's table: rows of
+    a sequence whose begin is negative stay unwritten, the other sequences are unaffected."""
+    Hq, Hkv = 32, 8
+    start = [1500, 2100, 900]
+    w = small_workload(726, mi.BF16, Hq, Hkv, [n + 1 for n in start], start)
+    pool, opool = DevPool(w), None
+    opool = oracle.new_pool(pool.shape)
+    fill_both(w, pool, opool)
+    db = DevBatch(w)
+    ws_bytes = mc.mc_attn_workspace_size(3, 3, Hq, Hkv)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    mc.mc_attn_plan_ahead(pool.desc, Hq, 3, 3, db.cu_q, db.begin, db.page_table, db.cu_pages, 0, ws,
+                          ws_bytes)
+    mc.mc_attn_plan_check(ws)
+    q = np.concatenate([w.q(s) for s in range(3)])
+    out = torch.full((3, Hq, 128), 0x7fc1, dtype=torch.int16, device=DEV)
+    lse = torch.full((3, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    stale = dev(np.array([-7, 2100, 3], dtype=np.int32))      # negative / as planned / far too small
+    mc.mc_prefix_prefill_attn(pool.desc, 0, dev(q), Hq, 3, 3, db.cu_q, stale, db.page_table,
+                              db.cu_pages, 0.0, out, lse, ws, ws_bytes)
+    torch.cuda.synchronize()
+    assert bool((out[0] == 0x7fc1).all()) and bool(torch.isnan(lse[0]).all())   # nothing written
+    ro, rl = oracle_rows(w, opool, pool.shape, 0, 1, w.q(1))
+    assert np.max(np.abs(oracle.decode(bits(out[1:2]), w.dtype) - ro)) <= O_TOL
+    assert np.max(np.abs(lse[1:2].cpu().numpy() - rl)) <= LSE_TOL
+    # sequence 2 now stands at 3 tokens: its row attends keys 0..3 of its own pages, as the oracle does
+    ro, rl = oracle.attention(opool, pool.shape, 0, w.page_tables[2], w.q(2), Hq, 3, 4)
+    assert np.max(np.abs(oracle.decode(bits(out[2:3]), w.dtype) - ro)) <= O_TOL
+    assert np.max(np.abs(lse[2:3].cpu().numpy() - rl)) <= LSE_TOL
 
 
 def test_bad_page_id_in_a_large_batch_is_reported():

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), n
     assert sorted(mc.EXPORTS) == names
-    assert mc.mc_abi_version() == 1
+    assert mc.mc_abi_version() == 2
     assert mc.status_string(0) == "MC_OK" and mc.status_string(3) == "MC_ERR_RANGE"
 
 
@@ -92,6 +92,17 @@ def _pool(**kw):
     d.update(kw)
     return mc.pool_desc(d.pop("base"), d.pop("num_layers"), d.pop("num_pages"),
                         d.pop("num_kv_heads"), d.pop("dtype"), **d)
+
+
+def test_copy_check_needs_a_counter():
+    # without a counter, or with a misaligned one, nothing is read from the device
+    L = mc.lib()
+    import ctypes as C
+    assert L.mc_kv_copy_check(None, None, None) == mc.MC_ERR_INVALID
+    assert L.mc_kv_copy_check(C.byref(_pool()), None, None) == mc.MC_ERR_INVALID
+    assert L.mc_kv_copy_check(C.byref(_pool(skipped=FAKE + 2)), None, None) == mc.MC_ERR_INVALID
+    # a misaligned counter is refused by every call that takes the pool
+    assert _status(mc.mc_kv_pack_range, _pool(skipped=FAKE + 2), 0, 1, FAKE, 4, 0, 16, FAKE) == mc.MC_ERR_INVALID
 
 
 def _status(fn, *args):

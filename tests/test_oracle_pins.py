@@ -441,7 +441,7 @@ def test_config_shapes(idx):
         assert list(w.n) == [16384, 32768] and w.num_layers == 32
 
 
-# ---- host arithmetic of remote_send (Sec. 3.4) ----
+# ---- host arithmetic of remote_send (Sec. 3.5) ----
 def test_send_plan_case1_sender_matched_more():
     # sender cached 300 tokens, receiver 100, request [0, 500): 100..299 exist only on the
     # sender and go as they are; 300..499 exist nowhere: computed, then sent
@@ -510,7 +510,7 @@ def test_prep_recv_oracle_allocates_only_the_unmatched_part():
     assert oracle.prep_recv(ix, al, [9] * 64, 64) is None and al.num_free == 2   # all or nothing
 
 
-# ---- fork_sequence (Sec. 3.4) ----
+# ---- fork_sequence (Sec. 3.5) ----
 def test_fork_sequence_oracle_hand_cases():
     al = oracle.Allocator(10)
     parent = al.take(7)                                  # pages 0..6 hold 100 tokens
