@@ -112,6 +112,23 @@ struct WorkspaceLayout {
 
 inline size_t round64(size_t x) { return (x + 63) & ~size_t(63); }
 
+// The attention kernel comes with q tiles of 128 rows (two workgroups per compute unit) and of
+// 256 rows (one, with every K/V fragment read from LDS feeding two MFMAs), the wide ones paying
+// off on long KV ranges only.  The planner chooses (it sees the lengths, the host does not) and
+// says so in the plan's header; the host only rules the wide tiles out where the batch cannot
+// want them - fewer than 4096 new tokens per sequence on average, or fewer wide tiles than four
+// per compute unit of a 256-unit GPU - and otherwise launches both kernels, of which the one
+// the plan was not made for returns at once.  The workspace is laid out for the narrow tiles
+// (more of them), which holds either plan.
+inline bool wide_tiles_allowed(int32_t batch, int32_t total_q, int G, int num_kv_heads) {
+#ifdef MC_WIDE_TILES
+  return MC_WIDE_TILES;
+#endif
+  const int64_t wide_tiles = ((int64_t)total_q * G + 2 * kBM - 1) / (2 * kBM);
+  return batch > 0 && total_q / batch >= 4096 && wide_tiles * num_kv_heads >= 1024;
+}
+constexpr int kWideMinKeys = 8192;   // mean keys per new token from which the planner goes wide
+
 constexpr int kMaxSlots = 1024;   // 512 compute units: beyond any GPU this library is written for
 constexpr size_t kPartialBytesCap = size_t(128) << 20;
 
@@ -162,6 +179,7 @@ struct PlanArgs {
   int32_t hkv, slots;   // kv heads; workgroups the GPU runs at a time
   int32_t allow_groups; // look for decode rows of neighbouring sequences that share a prefix
   int32_t ahead;        // tokens every sequence's begin may still grow by while the plan is in use
+  int32_t wide_tile_tokens, slots_wide;   // the wide q tiles, if the host allows them (else 0)
 };
 
 // Block-wide exclusive scan of one value per thread (kPlanThreads threads): a shuffle scan
@@ -291,9 +309,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   }
   __syncthreads();
 
-  // 1. validate, count tiles per sequence (contiguous chunk of sequences per thread)
   const int per = (a.batch + kPlanThreads - 1) / kPlanThreads;
   const int s_lo = min(t * per, a.batch), s_hi = min(s_lo + per, a.batch);
+  // 0. q tile width: wide tiles when a new token sees kWideMinKeys keys on average
+  if (a.wide_tile_tokens > 0) {
+    long long keys = 0, rows = 0;
+    for (int s = s_lo; s < s_hi; ++s) {
+      const long long q = a.cu_q[s + 1] - a.cu_q[s], b = a.begin[s];
+      if (q > 0 && b >= 0) { rows += q; keys += q * b + q * (q + 1) / 2; }
+    }
+    keys = block_sum(keys, scan);
+    rows = block_sum(rows, scan);
+    if (rows > 0 && keys / rows >= kWideMinKeys) {
+      a.tile_tokens = a.wide_tile_tokens;
+      a.slots = a.slots_wide;
+    }
+  }
+  // 1. validate, count tiles per sequence (contiguous chunk of sequences per thread)
   int my_tiles = 0, err = 0, maxcost = 1;
   if (t == 0 && (a.cu_q[0] != 0 || a.cu_q[a.batch] != a.total_q || a.cu_pages[0] < 0)) err = 1;
   for (int s = s_lo; s < s_hi; ++s) {
@@ -668,6 +700,15 @@ template <> struct Mfma<_Float16> {
   static __device__ __forceinline__ f32x16 run(vec8 a, vec8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
   }
+  // the same instruction with its result pinned to vector registers (see attn_kernel: with
+  // two row blocks the allocator would otherwise park the scores in accumulation registers,
+  // which the softmax's vector instructions cannot read)
+  static __device__ __forceinline__ void run_v0(vec8 a, vec8 b, f32x16& c) {
+    asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=v"(c) : "v"(a), "v"(b));
+  }
+  static __device__ __forceinline__ void run_v(vec8 a, vec8 b, f32x16& c) {
+    asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+  }
   static __device__ __forceinline__ uint32_t pack2(float x, float y) {
     typedef _Float16 h2 __attribute__((ext_vector_type(2)));
     h2 v;
@@ -680,6 +721,12 @@ template <> struct Mfma<__bf16> {
   typedef bf16x8 vec8;
   static __device__ __forceinline__ f32x16 run(vec8 a, vec8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ void run_v0(vec8 a, vec8 b, f32x16& c) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(c) : "v"(a), "v"(b));
+  }
+  static __device__ __forceinline__ void run_v(vec8 a, vec8 b, f32x16& c) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
   }
   static __device__ __forceinline__ uint32_t pack2(float x, float y) {
     typedef __bf16 b2 __attribute__((ext_vector_type(2)));
@@ -786,9 +833,13 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 // fetch (4 MFMAs ahead of its use) and a slice of the VALU work; the order is pinned.
 // kGate: wavefronts none of whose rows exists skip the arithmetic.  Worth it for batches with
 // many short q tiles (decode steps); the plain variant is ~2 % faster when all tiles are full.
-template <typename T, int G, bool kGate>
-__global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
-  constexpr int TOK = kBM / G;  // tokens per q tile
+// kCB: blocks of 32 rows per wavefront.  1: q tiles of 128 rows, two workgroups per compute
+// unit.  2: q tiles of 256 rows, one workgroup per compute unit with twice the registers: every
+// K and V fragment read from LDS feeds two MFMAs, every tile copied to LDS serves twice the rows.
+template <typename T, int G, bool kGate, int kCB>
+__global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnArgs a) {
+  constexpr int kWaveRows = 32 * kCB;       // rows per wavefront
+  constexpr int TOK = kBM * kCB / G;        // tokens per q tile
   constexpr int kHalf = kBN / 2;
   constexpr int kHalfBytes = kTileBytes / 2;
   typedef typename Mfma<T>::vec8 vec8;
@@ -847,23 +898,28 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   const int last_pidx = min((kv_len - 1) / kPage, table_len - 1);   // last entry that holds a needed key
   const_i32_ptr table = (const_i32_ptr)(a.page_table + a.cu_pages[seq]);
 
-  // this lane's query row
-  const int r = wave * 32 + l32;                     // row in tile
-  const int g = r % G, tt = r / G;                   // token-major: the rows of a short tile
-  const bool row_ok = tt < ntok;                     // (a decode step's G rows) fill whole waves
-  // a wavefront none of whose rows exists only helps with the copies and the barriers
-  const bool wave_active = !kGate || wave * 32 < ntok * G;
-  const int my_pos = first_pos + (row_ok ? tt : ntok - 1);   // causal limit of the row
-  const int64_t q_row = ((int64_t)(q0 + row0 + tt) * a.hq + hk * G + g) * kRowBytes;
-
+  // this lane's query rows, one per row block
+  int g[kCB], tt[kCB], my_pos[kCB];
+  bool row_ok[kCB];
   // Q as the B operand: lane holds d = 16 kk + 8 half + [0,8) of its row, kk = 0..7
-  vec8 qreg[8];
+  vec8 qreg[kCB][8];
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    u32x4 v = {0, 0, 0, 0};
-    if (row_ok) v = *reinterpret_cast<const u32x4*>(a.q + q_row + kk * 32 + half * 16);
-    qreg[kk] = __builtin_bit_cast(vec8, v);
+  for (int cb = 0; cb < kCB; ++cb) {
+    const int r = wave * kWaveRows + cb * 32 + l32;    // row in tile
+    g[cb] = r % G;                                     // token-major: the rows of a short tile
+    tt[cb] = r / G;                                    // (a decode step's G rows) fill whole waves
+    row_ok[cb] = tt[cb] < ntok;
+    my_pos[cb] = first_pos + (row_ok[cb] ? tt[cb] : ntok - 1);   // causal limit of the row
+    const int64_t q_row = ((int64_t)(q0 + row0 + tt[cb]) * a.hq + hk * G + g[cb]) * kRowBytes;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      u32x4 v = {0, 0, 0, 0};
+      if (row_ok[cb]) v = *reinterpret_cast<const u32x4*>(a.q + q_row + kk * 32 + half * 16);
+      qreg[cb][kk] = __builtin_bit_cast(vec8, v);
+    }
   }
+  // a wavefront none of whose rows exists only helps with the copies and the barriers
+  const bool wave_active = !kGate || wave * kWaveRows < ntok * G;
 
   // ---- global -> LDS copies (no VGPR staging) -------------------------------------
   // A wavefront's copy instruction fills 1 KiB of LDS linearly (lane L -> bytes 16 L..),
@@ -946,11 +1002,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   };
 
   // key held by accumulator register i of half h: 32 h + 8 (i/4) + 4 half + i%4
-  auto mask_half = [&](int h, f32x16& sc) __attribute__((always_inline)) {
+  auto mask_half = [&](int h, f32x16& sc, int cb) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int key = h * kHalf + 8 * (i >> 2) + 4 * half + (i & 3);
-      if (key > my_pos) sc[i] = -INFINITY;
+      if (key > my_pos[cb]) sc[i] = -INFINITY;
     }
   };
   // the other 16 keys of the row's half tile sit in lane l ^ 32: swap the wave's halves on the VALU
@@ -964,14 +1020,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     return fmaxf(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
   };
 
-  f32x16 o_acc[4];
-  float m_run, l_run;                     // reference score of the row (raw), this lane's partial sum
-  float mx_cur;                           // row max of the half tile about to be exponentiated
+  f32x16 o_acc[kCB][4];
+  float m_run[kCB], l_run[kCB];           // reference score of the row (raw), this lane's partial sum
+  float mx_cur[kCB];                      // row max of the half tile about to be exponentiated
   const float c2 = a.scale_log2;
   const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   constexpr int kAhead = 4;               // fragments in flight
   vec8 kf[kAhead];                        // first K fragments of the next phase 1
-  f32x16 s_a, s_b;
+  f32x16 s_a[kCB], s_b[kCB];
 
   // ---- one half step.  s_cur = S(h) in, s_next = S(h+1) out (computed even when half h+1
   //      does not exist: its LDS rows are then stale, the result is never used).
@@ -982,69 +1038,109 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   //      no row max, no rescale, and the exponentials of the last kPairsLate register pairs move
   //      into phase 2, whose VALU slots the row max no longer needs.
   auto half_step = [&](auto fixed_ref, int h, uint32_t k_next, bool fetch_after, uint32_t k_after,
-                       uint32_t v_cur, int crow, f32x16& s_cur, f32x16& s_next,
+                       uint32_t v_cur, int crow, f32x16 (&s_cur)[kCB], f32x16 (&s_next)[kCB],
                        bool mask_next, auto&& slot_extra) __attribute__((always_inline)) {
     constexpr bool kFixed = decltype(fixed_ref)::value;
-    constexpr int kLate = kFixed ? kPairsLate : 0;
+    constexpr int kPairs = 8 * kCB;                       // register pairs of S(h), all row blocks
+    constexpr int kLate = kFixed ? kPairsLate * kCB : 0;  // ... of which phase 2 takes this many
     vec8 vf[kAhead];
     if constexpr (!kFixed) {
       // ---- move the reference max (and rescale O, l) only when some row's max rose by more
       //      than 2^8 in the exp2 domain: p stays below 2^8, sums stay exact
-      if (__builtin_amdgcn_ballot_w64((mx_cur - m_run) * c2 > 8.f) != 0) {
-        const float m_new = fmaxf(m_run, mx_cur);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-        m_run = m_new;
-        l_run *= alpha;
+      bool moved = false;
 #pragma unroll
-        for (int dc = 0; dc < 4; ++dc)
+      for (int cb = 0; cb < kCB; ++cb) moved |= (mx_cur[cb] - m_run[cb]) * c2 > 8.f;
+      if (__builtin_amdgcn_ballot_w64(moved) != 0) {
 #pragma unroll
-          for (int i = 0; i < 16; ++i) o_acc[dc][i] *= alpha;
+        for (int cb = 0; cb < kCB; ++cb) {
+          const float m_new = fmaxf(m_run[cb], mx_cur[cb]);
+          const float alpha = __builtin_amdgcn_exp2f((m_run[cb] - m_new) * c2);
+          m_run[cb] = m_new;
+          l_run[cb] *= alpha;
+#pragma unroll
+          for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o_acc[cb][dc][i] *= alpha;
+        }
       }
     }
-    const float mc2 = m_run * c2;
-    uint32_t p_pk[8];
-    // softmax of register pair t of S(h) (registers 2t, 2t+1 -> packed operand word t).  The
-    // row sum takes the unrounded values: LSE must not inherit P's 2-byte rounding.  (The empty
-    // assembly statement keeps the additions here, beside their exponentials: left alone the
-    // compiler gathers them at the end of the half step and keeps all 16 values live until then.)
-    auto soft_pair = [&](int t) __attribute__((always_inline)) {
-      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[2 * t], c2, -mc2));
-      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[2 * t + 1], c2, -mc2));
-      l_run += p0 + p1;
-      asm volatile("" : "+v"(l_run));
-      p_pk[t] = Mfma<T>::pack2(p0, p1);
+    float mc2[kCB];
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb) mc2[cb] = m_run[cb] * c2;
+    uint32_t p_pk[kCB][8];
+    // softmax of register pair t of S(h) of row block cb (registers 2t, 2t+1 -> packed operand
+    // word t).  The row sum takes the unrounded values: LSE must not inherit P's 2-byte rounding.
+    // (The empty assembly statement keeps the additions here, beside their exponentials: left
+    // alone the compiler gathers them at the end of the half step and keeps all values live.)
+    auto soft_pair = [&](int cb, int t) __attribute__((always_inline)) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[cb][2 * t], c2, -mc2[cb]));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[cb][2 * t + 1], c2, -mc2[cb]));
+      l_run[cb] += p0 + p1;
+      asm volatile("" : "+v"(l_run[cb]));
+      p_pk[cb][t] = Mfma<T>::pack2(p0, p1);
+    };
+    // pairs in the order phase 2 needs them: words 0..3 of every row block, then words 4..7
+    auto soft_nth = [&](int i) __attribute__((always_inline)) {
+      soft_pair((i / 4) % kCB, (i / (4 * kCB)) * 4 + i % 4);
     };
     __builtin_amdgcn_sched_barrier(0);
-    // ---- phase 1: 8 steps.  Step t: d-step t of S(h+1); softmax of a register pair of S(h).
+    // ---- phase 1: 8 steps.  Step t: d-step t of S(h+1) for every row block (one K fragment
+    //      feeds kCB MFMAs); beside each MFMA the softmax of a register pair of S(h).
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-      if (t < 8 - kLate) soft_pair(t);
-      s_next = Mfma<T>::run(kf[t % kAhead], qreg[t], t == 0 ? zero16 : s_next);
+#pragma unroll
+      for (int cb = 0; cb < kCB; ++cb) {
+        if (t * kCB + cb < kPairs - kLate) soft_nth(t * kCB + cb);
+        if constexpr (kFixed && kCB == 2) {
+          // (nothing reads these registers before the next half step's softmax, a whole phase
+          // of MFMAs later, except the mask below, which waits for the matrix pipe first)
+          if (t == 0) Mfma<T>::run_v0(kf[t % kAhead], qreg[cb][t], s_next[cb]);
+          else Mfma<T>::run_v(kf[t % kAhead], qreg[cb][t], s_next[cb]);
+        } else {
+          s_next[cb] = Mfma<T>::run(kf[t % kAhead], qreg[cb][t], t == 0 ? zero16 : s_next[cb]);
+        }
+        if (cb + 1 < kCB) __builtin_amdgcn_sched_barrier(0);
+      }
       if (t + kAhead < 8) kf[t % kAhead] = k_frag(k_next, t + kAhead);
       else vf[t % kAhead] = v_frag(v_cur, crow, t + kAhead - 8);
       slot_extra(t);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (mask_next) mask_half(h + 1, s_next);
+    if (mask_next) {
+      // the scores may come from MFMAs the compiler does not see as such: let the last of them
+      // (8 passes of 4 cycles) leave the pipe before vector instructions rewrite its registers
+      if constexpr (kFixed && kCB == 2) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
+#pragma unroll
+      for (int cb = 0; cb < kCB; ++cb) mask_half(h + 1, s_next[cb], cb);
+    }
     // ---- phase 2: 8 steps.  Step u: V fragment u (16-key step st = u >> 2 -> operand words
-    //      4 st..4 st+3, d chunk dc = u & 3); row max over register pair u of S(h+1).
-    float mx;
+    //      4 st..4 st+3, d chunk dc = u & 3) for every row block; beside the MFMAs the row max
+    //      over register pair u of S(h+1), or the softmax pairs phase 1 left over.
+    float mx[kCB];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int st = u >> 2, dc = u & 3;
-      u32x4 pw = {p_pk[4 * st], p_pk[4 * st + 1], p_pk[4 * st + 2], p_pk[4 * st + 3]};
-      o_acc[dc] = Mfma<T>::run(vf[u % kAhead], __builtin_bit_cast(vec8, pw), o_acc[dc]);
+#pragma unroll
+      for (int cb = 0; cb < kCB; ++cb) {
+        u32x4 pw = {p_pk[cb][4 * st], p_pk[cb][4 * st + 1], p_pk[cb][4 * st + 2], p_pk[cb][4 * st + 3]};
+        o_acc[cb][dc] = Mfma<T>::run(vf[u % kAhead], __builtin_bit_cast(vec8, pw), o_acc[cb][dc]);
+        if constexpr (kFixed) {
+          if (u * kCB + cb < kLate) soft_nth(kPairs - kLate + u * kCB + cb);   // words 4..7: first read at step 4
+        } else {
+          mx[cb] = u == 0 ? fmaxf(s_next[cb][0], s_next[cb][1])
+                          : max3(mx[cb], s_next[cb][2 * u], s_next[cb][2 * u + 1]);
+        }
+        if (cb + 1 < kCB) __builtin_amdgcn_sched_barrier(0);
+      }
       if (u + kAhead < 8) vf[u % kAhead] = v_frag(v_cur, crow, u + kAhead);
       else if (fetch_after) kf[u % kAhead] = k_frag(k_after, u + kAhead - 8);
-      if constexpr (kFixed) {
-        if (u < kLate) soft_pair(8 - kLate + u);   // words 4..7 are first read at step 4
-      } else {
-        mx = u == 0 ? fmaxf(s_next[0], s_next[1]) : max3(mx, s_next[2 * u], s_next[2 * u + 1]);
-      }
       slot_extra(8 + u);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if constexpr (!kFixed) mx_cur = max_across_halves(mx);
+    if constexpr (!kFixed) {
+#pragma unroll
+      for (int cb = 0; cb < kCB; ++cb) mx_cur[cb] = max_across_halves(mx[cb]);
+    }
   };
 
   // ---- the copies of one tile.  par = j & 1 fixes every LDS address of the tile: K halves 2j+1,
@@ -1120,11 +1216,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   //      caller checks the row sums afterwards.
   auto run_pass = [&](auto fixed_ref) __attribute__((always_inline)) {
 #pragma unroll
-    for (int dc = 0; dc < 4; ++dc)
+    for (int cb = 0; cb < kCB; ++cb) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o_acc[dc][i] = 0.f;
-    m_run = -INFINITY;
-    l_run = 0.f;
+      for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[cb][dc][i] = 0.f;
+      m_run[cb] = -INFINITY;
+      l_run[cb] = 0.f;
+    }
     // ---- prologue: K halves 0, 1, 2 and V(0) in flight together; S(half 0) -------------
     {
       // table entries 0..5 (K halves 0..2), 0..3 (V tile 0)
@@ -1140,13 +1239,30 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     wait_copies_and_sync();
     if (wave_active) {
 #pragma unroll
-      for (int f = 0; f < 8; ++f) s_a = Mfma<T>::run(k_frag(lds_k, f), qreg[f], f == 0 ? zero16 : s_a);
-      if (n_full <= 2 * t0) mask_half(2 * t0, s_a);
-      float mx = fmaxf(s_a[0], s_a[1]);
+      for (int f = 0; f < 8; ++f) {
+        const vec8 kfr = k_frag(lds_k, f);
 #pragma unroll
-      for (int i = 2; i < 16; i += 2) mx = max3(mx, s_a[i], s_a[i + 1]);
-      mx_cur = max_across_halves(mx);
-      if constexpr (decltype(fixed_ref)::value) m_run = mx_cur;
+        for (int cb = 0; cb < kCB; ++cb) {
+          if constexpr (decltype(fixed_ref)::value && kCB == 2) {
+            if (f == 0) Mfma<T>::run_v0(kfr, qreg[cb][f], s_a[cb]);
+            else Mfma<T>::run_v(kfr, qreg[cb][f], s_a[cb]);
+          } else {
+            s_a[cb] = Mfma<T>::run(kfr, qreg[cb][f], f == 0 ? zero16 : s_a[cb]);
+          }
+        }
+      }
+      // (MFMAs written as assembly: the matrix pipe must have drained before their results are read)
+      if constexpr (decltype(fixed_ref)::value && kCB == 2)
+        asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
+#pragma unroll
+      for (int cb = 0; cb < kCB; ++cb) {
+        if (n_full <= 2 * t0) mask_half(2 * t0, s_a[cb], cb);
+        float mx = fmaxf(s_a[cb][0], s_a[cb][1]);
+#pragma unroll
+        for (int i = 2; i < 16; i += 2) mx = max3(mx, s_a[cb][i], s_a[cb][i + 1]);
+        mx_cur[cb] = max_across_halves(mx);
+        if constexpr (decltype(fixed_ref)::value) m_run[cb] = mx_cur[cb];
+      }
     }
     __syncthreads();   // every wave has read K half 0 before tile 0 overwrites its slot
 
@@ -1204,13 +1320,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
     // overflowed (or is not a number) sends the whole workgroup through the pass again with the
     // moving reference; on scores like the workloads' (a few units wide) that never happens.
     run_pass(std::true_type{});
-    const float l_chk = l_run + __shfl_xor(l_run, 32);
+    bool sums_ok = true;
     float o_chk = 0.f;                     // NaN if any accumulator is infinite or not a number
 #pragma unroll
-    for (int dc = 0; dc < 4; ++dc)
+    for (int cb = 0; cb < kCB; ++cb) {
+      sums_ok = sums_ok && l_run[cb] + __shfl_xor(l_run[cb], 32) < kFixedRefSumLimit;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o_chk = __builtin_fmaf(o_acc[dc][i], 0.f, o_chk);
-    const bool bad = wave_active && !(l_chk < kFixedRefSumLimit && o_chk == 0.f);
+      for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_chk = __builtin_fmaf(o_acc[cb][dc][i], 0.f, o_chk);
+    }
+    const bool bad = wave_active && !(sums_ok && o_chk == 0.f);
     if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) s_redo = 1;
     __syncthreads();
     if (s_redo != 0) run_pass(std::false_type{});
@@ -1220,51 +1340,66 @@ __global__ __launch_bounds__(kThreads, 2) void attn_kernel(AttnArgs a) {
   if (kGate && !wave_active) return;
 
   // ---- epilogue: normalise, stage O through LDS for full-row stores, write LSE ----
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  const float inv = 1.f / l_tot;
+  float l_tot[kCB], inv[kCB];
+#pragma unroll
+  for (int cb = 0; cb < kCB; ++cb) {
+    l_tot[cb] = l_run[cb] + __shfl_xor(l_run[cb], 32);
+    inv[cb] = 1.f / l_tot[cb];
+  }
   if (part >= 0) {
     // One chunk of a cut KV range: O normalised within the chunk (fp32) and the chunk's LSE go
     // to the partial arrays; merge_kernel weighs the chunks together.  A lane holds, for its
     // row, d = 32 dc + 8 j + 4 half + {0..3}: 16 bytes per (dc, j).
-    if (row_ok) {
-      const int64_t prow = (int64_t)(part + tt) * a.hq + hk * G + g;
+#pragma unroll
+    for (int cb = 0; cb < kCB; ++cb) {
+      if (!row_ok[cb]) continue;
+      const int64_t prow = (int64_t)(part + tt[cb]) * a.hq + hk * G + g[cb];
       float* po = a.part_o + prow * mc::kHeadDim;
 #pragma unroll
       for (int dc = 0; dc < 4; ++dc)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           typedef float f32x4 __attribute__((ext_vector_type(4)));
-          f32x4 v = {o_acc[dc][4 * j] * inv, o_acc[dc][4 * j + 1] * inv, o_acc[dc][4 * j + 2] * inv,
-                     o_acc[dc][4 * j + 3] * inv};
+          f32x4 v = {o_acc[cb][dc][4 * j] * inv[cb], o_acc[cb][dc][4 * j + 1] * inv[cb],
+                     o_acc[cb][dc][4 * j + 2] * inv[cb], o_acc[cb][dc][4 * j + 3] * inv[cb]};
           *reinterpret_cast<f32x4*>(po + 32 * dc + 8 * j + 4 * half) = v;
         }
-      if (half == 0) a.part_lse[prow] = m_run * a.scale + __logf(l_tot);
+      if (half == 0) a.part_lse[prow] = m_run[cb] * a.scale + __logf(l_tot[cb]);
     }
     return;
   }
-  char* stage = lds + wave * (32 * kRowBytes);   // 8 KiB per wave; all tiles are consumed
+  // 8 KiB per wave and row block; all tiles are consumed
 #pragma unroll
-  for (int dc = 0; dc < 4; ++dc)
+  for (int cb = 0; cb < kCB; ++cb) {
+    char* stage = lds + (wave * kCB + cb) * (32 * kRowBytes);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      // registers 4j..4j+3 hold d = 32 dc + 8 j + 4 half + {0..3}: 8 bytes of chunk 4 dc + j
-      u32x2 w;
-      w[0] = Mfma<T>::pack2(o_acc[dc][4 * j] * inv, o_acc[dc][4 * j + 1] * inv);
-      w[1] = Mfma<T>::pack2(o_acc[dc][4 * j + 2] * inv, o_acc[dc][4 * j + 3] * inv);
-      *reinterpret_cast<u32x2*>(stage + k_swz(l32, 4 * dc + j) + half * 8) = w;
-    }
-  if (row_ok && half == 0)
-    a.lse[(int64_t)(q0 + row0 + tt) * a.hq + hk * G + g] = m_run * a.scale + __logf(l_tot);
+    for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        // registers 4j..4j+3 hold d = 32 dc + 8 j + 4 half + {0..3}: 8 bytes of chunk 4 dc + j
+        u32x2 w;
+        w[0] = Mfma<T>::pack2(o_acc[cb][dc][4 * j] * inv[cb], o_acc[cb][dc][4 * j + 1] * inv[cb]);
+        w[1] = Mfma<T>::pack2(o_acc[cb][dc][4 * j + 2] * inv[cb], o_acc[cb][dc][4 * j + 3] * inv[cb]);
+        *reinterpret_cast<u32x2*>(stage + k_swz(l32, 4 * dc + j) + half * 8) = w;
+      }
+    if (row_ok[cb] && half == 0)
+      a.lse[(int64_t)(q0 + row0 + tt[cb]) * a.hq + hk * G + g[cb]] =
+          m_run[cb] * a.scale + __logf(l_tot[cb]);
+  }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int lr = 4 * i + (lane >> 4);               // row of this wave's 32
-    const int rr = wave * 32 + lr, gg = rr % G, t2 = rr / G;
-    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + k_swz(lr, lane & 15));
-    if (t2 < ntok)
-      *reinterpret_cast<u32x4*>(a.out + ((int64_t)(q0 + row0 + t2) * a.hq + hk * G + gg) * kRowBytes +
-                                (lane & 15) * 16) = v;
+  for (int cb = 0; cb < kCB; ++cb) {
+    const char* stage = lds + (wave * kCB + cb) * (32 * kRowBytes);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int lr = 4 * i + (lane >> 4);               // row of this block's 32
+      const int rr = wave * kWaveRows + cb * 32 + lr, gg = rr % G, t2 = rr / G;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(stage + k_swz(lr, lane & 15));
+      if (t2 < ntok)
+        *reinterpret_cast<u32x4*>(a.out + ((int64_t)(q0 + row0 + t2) * a.hq + hk * G + gg) * kRowBytes +
+                                  (lane & 15) * 16) = v;
+    }
   }
 }
 
@@ -1329,41 +1464,43 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   }
 }
 
-template <typename T, bool kGate>
+template <typename T, bool kGate, int kCB>
 mc_status launch_attn_g(int G, dim3 grid, hipStream_t hs, const AttnArgs& a) {
   switch (G) {
-    case 1: hipLaunchKernelGGL((attn_kernel<T, 1, kGate>), grid, dim3(kThreads), 0, hs, a); break;
-    case 2: hipLaunchKernelGGL((attn_kernel<T, 2, kGate>), grid, dim3(kThreads), 0, hs, a); break;
-    case 4: hipLaunchKernelGGL((attn_kernel<T, 4, kGate>), grid, dim3(kThreads), 0, hs, a); break;
-    case 8: hipLaunchKernelGGL((attn_kernel<T, 8, kGate>), grid, dim3(kThreads), 0, hs, a); break;
+    case 1: hipLaunchKernelGGL((attn_kernel<T, 1, kGate, kCB>), grid, dim3(kThreads), 0, hs, a); break;
+    case 2: hipLaunchKernelGGL((attn_kernel<T, 2, kGate, kCB>), grid, dim3(kThreads), 0, hs, a); break;
+    case 4: hipLaunchKernelGGL((attn_kernel<T, 4, kGate, kCB>), grid, dim3(kThreads), 0, hs, a); break;
+    case 8: hipLaunchKernelGGL((attn_kernel<T, 8, kGate, kCB>), grid, dim3(kThreads), 0, hs, a); break;
     default: return MC_ERR_UNSUPPORTED;
   }
   return mc::launch_status();
 }
 
 template <typename T>
-mc_status launch_attn(int G, bool gate, dim3 grid, hipStream_t hs, const AttnArgs& a) {
-  return gate ? launch_attn_g<T, true>(G, grid, hs, a) : launch_attn_g<T, false>(G, grid, hs, a);
+mc_status launch_attn(int G, bool gate, int row_blocks, dim3 grid, hipStream_t hs, const AttnArgs& a) {
+  if (row_blocks == 2) return launch_attn_g<T, false, 2>(G, grid, hs, a);
+  return gate ? launch_attn_g<T, true, 1>(G, grid, hs, a) : launch_attn_g<T, false, 1>(G, grid, hs, a);
 }
 
-// Workgroups of the attention kernel the current GPU runs at a time: two per compute unit.
+// Workgroups of the attention kernel the current GPU runs at a time: two per compute unit
+// (one with the wide q tiles).
 // The compute-unit count is asked for once per device (the query costs microseconds, which a
 // decode step notices); the current device is a thread-local read.
-int device_slots() {
+int device_slots(int row_blocks = 1) {
   constexpr int kDevs = 64;
   static std::atomic<int> cached[kDevs];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0) return -1;
   if (dev < kDevs) {
     const int c = cached[dev].load(std::memory_order_relaxed);
-    if (c > 0) return c;
+    if (c > 0) return row_blocks == 2 ? c / 2 : c;
   }
   int cus = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
       cus <= 0)
     return -1;
   if (dev < kDevs) cached[dev].store(2 * cus, std::memory_order_relaxed);
-  return 2 * cus;
+  return row_blocks == 2 ? cus : 2 * cus;
 }
 
 // The planner cuts KV ranges only if the q tiles times kv heads are fewer than kRoundsWanted per
@@ -1411,8 +1548,9 @@ mc_status plan_impl(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch
   mc_status st = check_attn_shape(pool, num_q_heads, batch, total_q, &G);
   if (st != MC_OK) return st;
   if (!workspace || !mc::aligned16(workspace)) return MC_ERR_INVALID;
+  const int tile_tokens = kBM / G;
   const WorkspaceLayout w =
-      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads, part_limit);
+      workspace_layout(batch, total_q, tile_tokens, num_q_heads, pool->num_kv_heads, part_limit);
   if (workspace_bytes < w.total) return MC_ERR_INVALID;
   if (batch > 0 && (!cu_q || !begin || !page_table || !cu_pages)) return MC_ERR_INVALID;
   if (batch == 0) {   // nothing to plan: a header with an empty work list
@@ -1430,13 +1568,16 @@ mc_status plan_impl(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch
   a.merges = reinterpret_cast<MergeRec*>(ws + w.merges);
   a.batch = batch;
   a.total_q = total_q;
-  a.tile_tokens = kBM / G;
+  a.tile_tokens = tile_tokens;
   a.num_pages = pool->num_pages;
   a.max_tiles = w.max_tiles;
   a.hkv = pool->num_kv_heads;
-  a.slots = device_slots();
+  a.slots = device_slots(1);
   if (a.slots <= 0) return MC_ERR_HIP;
-  a.allow_groups = may_group(w, total_q, kBM / G);
+  const bool wide = wide_tiles_allowed(batch, total_q, G, pool->num_kv_heads);
+  a.wide_tile_tokens = wide ? 2 * tile_tokens : 0;
+  a.slots_wide = device_slots(2);
+  a.allow_groups = may_group(w, total_q, tile_tokens);
   a.max_items = item_bound(w, a.hkv, a.slots, a.allow_groups);
   a.part_cap = w.part_cap;
   a.ahead = ahead_tokens;
@@ -1465,12 +1606,13 @@ mc_status attn_impl(const mc_pool_desc* pool, int32_t layer, const void* q, int3
   if (!mc::aligned16(q) || !mc::aligned16(out) || !mc::aligned16(workspace) ||
       (reinterpret_cast<uintptr_t>(lse) & 3u))
     return MC_ERR_INVALID;
+  const int tile_tokens = kBM / G;
   const WorkspaceLayout w =
-      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads, part_limit);
+      workspace_layout(batch, total_q, tile_tokens, num_q_heads, pool->num_kv_heads, part_limit);
   if (workspace_bytes < w.total) return MC_ERR_INVALID;
-  const int slots = device_slots();
+  const int slots = device_slots(1);
   if (slots <= 0) return MC_ERR_HIP;
-  const bool groups = may_group(w, total_q, kBM / G);
+  const bool groups = may_group(w, total_q, tile_tokens);
   const int64_t blocks =
       (int64_t)item_bound(w, pool->num_kv_heads, slots, groups) * pool->num_kv_heads;
   if (blocks > 0x7fffffffll) return MC_ERR_UNSUPPORTED;
@@ -1500,8 +1642,15 @@ mc_status attn_impl(const mc_pool_desc* pool, int32_t layer, const void* q, int3
   hipStream_t hs = static_cast<hipStream_t>(stream);
   // many sequences for the number of q tiles: a good share of the tiles is short
   const bool gate = 4ll * batch >= w.max_tiles - batch;
-  st = pool->dtype == MC_F16 ? launch_attn<_Float16>(G, gate, grid, hs, a)
-                             : launch_attn<__bf16>(G, gate, grid, hs, a);
+  st = pool->dtype == MC_F16 ? launch_attn<_Float16>(G, gate, 1, grid, hs, a)
+                             : launch_attn<__bf16>(G, gate, 1, grid, hs, a);
+  if (st == MC_OK && wide_tiles_allowed(batch, total_q, G, pool->num_kv_heads)) {
+    // the plan may be one of wide q tiles (fewer items than the grid's bound, which holds for
+    // either width): that kernel, too; the one the plan was not made for finds the other tile
+    // size in the header and returns
+    st = pool->dtype == MC_F16 ? launch_attn<_Float16>(G, false, 2, grid, hs, a)
+                               : launch_attn<__bf16>(G, false, 2, grid, hs, a);
+  }
   if (st != MC_OK || !(may_cut(w, pool->num_kv_heads, slots) || groups)) return st;
   // the planner may have cut KV ranges: weigh the chunks together (does nothing if it did not)
   MergeArgs m;
@@ -1512,7 +1661,7 @@ mc_status attn_impl(const mc_pool_desc* pool, int32_t layer, const void* q, int3
   m.out = a.out;
   m.lse = a.lse;
   m.hq = num_q_heads;
-  m.tile_tokens = kBM / G;
+  m.tile_tokens = tile_tokens;
   // one workgroup per (token, four q heads) pair if they all run at once, else a grid-stride walk
   const int64_t pairs = (int64_t)total_q * ((num_q_heads + 3) / 4);
   const dim3 mgrid((unsigned)(pairs < 4ll * slots ? pairs : 4ll * slots));
@@ -1610,13 +1759,14 @@ mc_status mc_prefix_prefill_attn_noalloc(const mc_pool_desc* pool, int32_t layer
   if (st != MC_OK) return st;
   // the work list alone must fit; what is left holds partial rows (32-byte item record, LSE
   // and O per row and q head), fewer than the caller-workspace variant may ask for
+  const int tile_tokens = kBM / G;
   const WorkspaceLayout fixed =
-      workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads, 0);
+      workspace_layout(batch, total_q, tile_tokens, num_q_heads, pool->num_kv_heads, 0);
   if (fixed.total + 4096 > kScratchBytes) return MC_ERR_RANGE;
   const size_t per_row = sizeof(ItemRec) + sizeof(float) * (size_t)num_q_heads * (mc::kHeadDim + 1);
   int32_t part_limit = (int32_t)((kScratchBytes - fixed.total - 4096) / per_row);
   while (part_limit > 0 &&
-         workspace_layout(batch, total_q, kBM / G, num_q_heads, pool->num_kv_heads, part_limit)
+         workspace_layout(batch, total_q, tile_tokens, num_q_heads, pool->num_kv_heads, part_limit)
                  .total > kScratchBytes)
     --part_limit;
   void* ws = nullptr;
