@@ -944,32 +944,26 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
   auto copy_page = [&](const char* base, bool is_v, uint32_t lds_page) __attribute__((always_inline)) {   // 16 rows = 4 KiB
     copy16_to_lds(base, is_v ? v_lane_off : k_lane_off, lds_page + wave * 1024);
   };
-  // ---- the page-id register -----------------------------------------------------------
+  // ---- the page ids of the next copies -----------------------------------------------
   // The page ids of a tile's copies are fetched one tile early by a vector load (lane i & 7
-  // holds table entry first + i) that is issued, like the copies, as an assembly statement: the
-  // compiler does not count it and places no wait for it.  Everything that touches the register
-  // is in this struct, and the three steps have one legal order:
-  //   issue(first)  the load is in flight; the register must not be read
-  //   arrive()      s_waitcnt vmcnt(0), with the register as an in/out operand of the statement:
-  //                 every later read depends on it and cannot be scheduled above the wait (the
-  //                 same wait covers the tile's global -> LDS copies, hence the barrier after it)
-  //   value()       the ids; only between an arrive() and the next issue()
-  // A register copy of `reg` made between issue() and arrive() would read a stale value: there
-  // is none, because nothing outside these methods names it.
+  // holds table entry first + i).  It is an ordinary load, which the compiler tracks: wherever
+  // the value is next needed (or moved, or spilled) the compiler waits for it, and since memory
+  // operations complete in the order of their issue that wait also covers the copies issued
+  // before it, which the compiler does not know of.  (As an untracked assembly load the register
+  // could be spilled, under register pressure, before its data had arrived.)  arrive() is the
+  // explicit wait for the copies - assembly statements, uncounted by the compiler - ahead of
+  // the workgroup barrier.
   const int32_t* table_g = a.page_table + a.cu_pages[seq];
   struct PageIds {
     int32_t reg;
     const int32_t* table;
     int lane7, last;
     __device__ __forceinline__ void issue(int first) {
-      const int32_t* p = table + min(first + lane7, last);
-      asm volatile("global_load_dword %0, %1, off" : "=v"(reg) : "v"(p) : "memory");
+      reg = __builtin_nontemporal_load(table + min(first + lane7, last));
     }
-    __device__ __forceinline__ void arrive() {
-      asm volatile("s_waitcnt vmcnt(0)" : "+v"(reg) : : "memory");
-    }
+    __device__ __forceinline__ void arrive() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
     __device__ __forceinline__ int32_t value() const { return reg; }
-  } ids;                                  // table entries 4j+4 .. 4j+11 during tile j
+  } ids;                                  // table entries of the next tile's copies
   ids.table = table_g;
   ids.lane7 = lane & 7;
   ids.last = last_pidx;
