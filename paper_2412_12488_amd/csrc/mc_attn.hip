@@ -1422,11 +1422,16 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   typedef float f32x2 __attribute__((ext_vector_type(2)));
   for (int64_t wk = blockIdx.x; wk < total; wk += gridDim.x) {
     const int tok = (int)(wk / head_groups), h = (int)(wk % head_groups) * 4 + wave;
-    // the record whose token range [tok_off, tok_off + ntok) holds tok
-    int lo = 0, hi = n_rec;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (a.merges[mid].tok_off <= tok) lo = mid; else hi = mid;
+    // the record whose token range [tok_off, tok_off + ntok) holds tok: a search that looks at
+    // 64 records per round, one per lane (one memory latency for up to 64 records, two for 4096)
+    int lo = 0, cnt = n_rec;
+    while (cnt > 1) {
+      const int step = (cnt + 63) / 64, end = lo + cnt;
+      const int i = lo + lane * step;
+      const bool le = i < end && a.merges[i].tok_off <= tok;
+      const int k = max(__popcll(__ballot(le)) - 1, 0);   // tok_off rises with the record index
+      lo += k * step;
+      cnt = min(step, end - lo);
     }
     const MergeRec m = a.merges[lo];
     const int tt = tok - m.tok_off;
@@ -1437,18 +1442,34 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
                                       : m.part + (c - m.g_nsplit) * m.ntok + tt) * a.hq + h;
     };
     const int nchunks = m.g_nsplit + m.nsplit;
+    // the chunks' LSEs: one per lane (in rounds of 64), so that their loads are in flight
+    // together instead of one after the other; the maximum by a butterfly over the wavefront
     float mx = -INFINITY;
-    for (int c = 0; c < nchunks; ++c) mx = fmaxf(mx, a.part_lse[row_of(c)]);
+    for (int c0 = 0; c0 < nchunks; c0 += 64) {
+      const int c = c0 + lane;
+      mx = fmaxf(mx, c < nchunks ? a.part_lse[row_of(c)] : -INFINITY);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     if (!(mx > -INFINITY)) continue;   // no chunk of this row was computed: nothing to write
     float den = 0.f;
     f32x2 acc = {0.f, 0.f};
-#pragma unroll 4
-    for (int c = 0; c < nchunks; ++c) {
-      const int64_t prow = row_of(c);
-      const float w = __expf(a.part_lse[prow] - mx);   // exp(-inf) = 0 for a chunk with no key
-      const f32x2 v = *reinterpret_cast<const f32x2*>(a.part_o + prow * mc::kHeadDim + 2 * lane);
-      den += w;
-      acc += v * w;
+    for (int c0 = 0; c0 < nchunks; c0 += 64) {
+      const int c = c0 + lane;
+      // exp(-inf) = 0 for a chunk with no key, and for the lanes beyond the last chunk
+      const float w_lane = c < nchunks ? __expf(a.part_lse[row_of(c)] - mx) : 0.f;
+      float sum = w_lane;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+      den += sum;
+      const int n = min(64, nchunks - c0);
+#pragma unroll 8
+      for (int k = 0; k < n; ++k) {
+        const float w = __shfl(w_lane, k);
+        const f32x2 v =
+            *reinterpret_cast<const f32x2*>(a.part_o + row_of(c0 + k) * mc::kHeadDim + 2 * lane);
+        acc += v * w;
+      }
     }
     const float inv = 1.f / den;
     const int64_t orow = (int64_t)(m.q_row + tt) * a.hq + h;
