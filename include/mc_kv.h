@@ -245,7 +245,7 @@ mc_status mc_prefix_prefill_attn(const mc_pool_desc* pool, int32_t layer,
  * (one copy per GPU the library has run on, held until the process ends).  The
  * call allocates nothing and does not synchronise.
  *   - Limit: the work list of the batch must fit the array - MC_ERR_RANGE, nothing
- *     launched, for batches beyond about 100000 q tiles; the room left over holds
+ *     launched, for batches beyond about 80000 q tiles; the room left over holds
  *     partial results, so KV ranges are cut into fewer chunks than with a full
  *     workspace (the results agree within the rounding of the merge).
  *   - There is no blocking check: malformed offsets, short tables or page ids

@@ -79,10 +79,17 @@ static_assert(sizeof(PlanHeader) == 64, "header is 64 bytes");
 // starting at seq (neighbours in the q array: tokens cu_q[seq] .. cu_q[seq] + gsize - 1), whose
 // page tables begin with the same pages; it covers tiles of that common prefix (all of it
 // visible to every row) and always writes partial rows.
+// The record also carries what the kernel needs to start its first copies without further
+// look-ups (each would be one more dependent memory round trip before the first tile): the
+// tile's first token in the q array and its token count, where the sequence's page table starts,
+// the last table entry the plan has validated for the sequence, and the page ids of table
+// entries 4 t0 .. 4 t0 + 5 (clamped to that last entry).
 struct ItemRec {
-  int32_t seq, row0, t0, t1, part, gsize, pad[2];
+  int32_t seq, row0, t0, t1, part, gsize;
+  int32_t q_first, ntok, table_off, pidx_cap;
+  int32_t ids[6];
 };
-static_assert(sizeof(ItemRec) == 32, "item record is 32 bytes");
+static_assert(sizeof(ItemRec) == 64, "item record is 64 bytes");
 
 // One q tile with partial results: chunk c of its own KV range has its partial rows at
 // part + c * ntok; if the tile's sequence belongs to a shared-prefix group, chunk c of the
@@ -654,6 +661,21 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       mtok_off += x.ntok;
       a.merges[merge_off++] = m;
     }
+    // what every item of this tile's sequence shares
+    const int sq0 = cu_in_lds ? s_cuq[x.s] : a.cu_q[x.s];
+    const int sq_len = (cu_in_lds ? s_cuq[x.s + 1] : a.cu_q[x.s + 1]) - sq0;
+    const int sb = cu_in_lds ? s_beg[x.s] : a.begin[x.s];
+    const int tab = cu_in_lds ? s_cup[x.s] : a.cu_pages[x.s];
+    const int cap = (int)(((int64_t)sb + sq_len + a.ahead + kPage - 1) / kPage) - 1;   // validated above
+    auto finish = [&](ItemRec& it, int q_first, int ntok) {
+      it.q_first = q_first;
+      it.ntok = ntok;
+      it.table_off = tab;
+      it.pidx_cap = cap;
+#pragma unroll
+      for (int k = 0; k < 6; ++k) it.ids[k] = a.page_table[tab + min(4 * it.t0 + k, cap)];
+      a.items[atomicAdd(&hist[bucket(it.t1 - it.t0)], 1)] = it;
+    };
     for (int c = 0; c < ns; ++c) {
       ItemRec it;
       it.seq = x.s;
@@ -662,8 +684,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       it.t1 = (c + 1 < ns ? x.pt + (c + 1) * Li : x.T);
       it.part = merged ? own_off + c * x.ntok : -1;
       it.gsize = 0;
-      it.pad[0] = it.pad[1] = 0;
-      a.items[atomicAdd(&hist[bucket(it.t1 - it.t0)], 1)] = it;
+      finish(it, sq0 + x.row0, x.ntok);
     }
     for (int c = 0; x.gm && c < ng; ++c) {
       ItemRec it;
@@ -673,8 +694,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       it.t1 = Li > 0 ? min((c + 1) * Li, x.pt) : x.pt;
       it.part = s_gbase[x.s] + c * x.gm;
       it.gsize = x.gm;
-      it.pad[0] = it.pad[1] = 0;
-      a.items[atomicAdd(&hist[bucket(it.t1 - it.t0)], 1)] = it;
+      finish(it, sq0, x.gm);
     }
     if (merged) own_off += ns * x.ntok;
   }
@@ -849,6 +869,11 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
 
   const int hk = blockIdx.x % a.hkv;
   const int wi = blockIdx.x / a.hkv;
+  // The item record is requested together with the plan's header (the grid never exceeds the
+  // room for records, whatever the header says): one memory round trip instead of two.
+  typedef int32_t i32x8 __attribute__((ext_vector_type(8)));
+  const auto* rec = (const __attribute__((address_space(4))) i32x8*)(a.items + wi);
+  const i32x8 item = rec[0], item_b = rec[1];
   // the work list must come from a plan made for this very batch
   if (a.hdr->magic != kPlanMagic || wi >= a.hdr->num_items || a.hdr->tile_tokens != TOK ||
       a.hdr->batch != a.batch || a.hdr->total_q != a.total_q)
@@ -859,22 +884,24 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
 
-  typedef int32_t i32x8 __attribute__((ext_vector_type(8)));
-  const i32x8 item = *(const __attribute__((address_space(4))) i32x8*)(a.items + wi);
   const int seq = item[0], row0 = item[1];
   const int t0 = item[2];                            // first KV tile of the item (even)
   const int part = item[4];                          // >= 0: partial result, merged afterwards
-  const int gsize = item[5];                         // > 0: shared-prefix item over gsize sequences
+  const int gsize = item[5];                         // > 0: shared-prefix item over gsize tokens
+  const int q_first = item[6];                       // the tile's first token in the q array
+  const int ntok = item[7];                          // valid tokens in this tile (>= 1)
+  const int table_off = item_b[0], pidx_cap = item_b[1];
   // a record that cannot come from the planner (a workspace written over by something else)
   if ((unsigned)seq >= (unsigned)a.batch || row0 < 0 || t0 < 0 || item[3] <= t0 || gsize < 0 ||
-      gsize > TOK)
+      gsize > TOK || ntok < 1 || ntok > TOK || (gsize > 0 && ntok != gsize) || q_first < 0 ||
+      (int64_t)q_first + ntok > a.total_q || table_off < 0 || pidx_cap < 0)
     return;
-  const int q0 = a.cu_q[seq], q_len = a.cu_q[seq + 1] - q0, b = a.begin[seq];
-  if (q0 < 0 || (int64_t)q0 + gsize > a.total_q) return;   // a group's rows are tokens of the q array
-  // valid tokens in this tile (>= 1), and the position of the first one.  The rows of a
-  // shared-prefix item are the new tokens of gsize consecutive sequences; all of them lie
-  // beyond the prefix, so any position at or past the item's last key serves.
-  const int ntok = gsize > 0 ? gsize : min(TOK, q_len - row0);
+  // begin is read here, not taken from the plan (one plan may serve many decode steps); it is
+  // the only look-up between the record and the first copies
+  const int b = a.begin[seq];
+  // The position of the tile's first token.  The rows of a shared-prefix item are new tokens of
+  // consecutive sequences; all of them lie beyond the prefix, so any position at or past the
+  // item's last key serves.
   const int first_pos = gsize > 0 ? item[3] * kBN : b + row0;
   // keys [64 t0, kv_len) are this item's: up to the end of its chunk, or of the tile's range
   const int kv_len = min(first_pos + ntok, item[3] * kBN);
@@ -882,21 +909,18 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
   const int n_halves = (kv_len + kHalf - 1) / kHalf;
   // half h is fully visible to every row of the q tile iff 32 (h+1) <= first_pos + 1
   const int n_full = (first_pos + 1) / kHalf;
-  // begin is read here, not taken from the plan (one plan may serve many decode steps): a value
-  // that no longer fits the item - negative, or so small that the item's first tile lies past
-  // the range - ends the workgroup before any table entry is read; table indices never leave
-  // the sequence's own slice of the page table
-  const int table_len = a.cu_pages[seq + 1] - a.cu_pages[seq];
-  if (b < 0 || ntok <= 0 || kv_len <= kBN * t0 || table_len <= 0) {
+  // A begin that no longer fits the item - negative, or so small that the item's first tile
+  // lies past the range - ends the workgroup before any page is read; table indices never
+  // pass the last entry the plan validated for the sequence.
+  if (b < 0 || kv_len <= kBN * t0) {
     // a chunk that is not computed says so in its partial rows (no key seen: LSE = -inf), so
     // that the merge gives it no weight, and writes nothing if no chunk of the row was computed
-    if (part >= 0 && ntok > 0)
+    if (part >= 0)
       for (int i = tid; i < ntok * G; i += kThreads)
         a.part_lse[(int64_t)(part + i / G) * a.hq + hk * G + i % G] = -INFINITY;
     return;
   }
-  const int last_pidx = min((kv_len - 1) / kPage, table_len - 1);   // last entry that holds a needed key
-  const_i32_ptr table = (const_i32_ptr)(a.page_table + a.cu_pages[seq]);
+  const int last_pidx = min((kv_len - 1) / kPage, pidx_cap);   // last entry that holds a needed key
 
   // this lane's query rows, one per row block
   int g[kCB], tt[kCB], my_pos[kCB];
@@ -910,7 +934,7 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
     tt[cb] = r / G;                                    // (a decode step's G rows) fill whole waves
     row_ok[cb] = tt[cb] < ntok;
     my_pos[cb] = first_pos + (row_ok[cb] ? tt[cb] : ntok - 1);   // causal limit of the row
-    const int64_t q_row = ((int64_t)(q0 + row0 + tt[cb]) * a.hq + hk * G + g[cb]) * kRowBytes;
+    const int64_t q_row = ((int64_t)(q_first + tt[cb]) * a.hq + hk * G + g[cb]) * kRowBytes;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       u32x4 v = {0, 0, 0, 0};
@@ -953,7 +977,7 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
   // could be spilled, under register pressure, before its data had arrived.)  arrive() is the
   // explicit wait for the copies - assembly statements, uncounted by the compiler - ahead of
   // the workgroup barrier.
-  const int32_t* table_g = a.page_table + a.cu_pages[seq];
+  const int32_t* table_g = a.page_table + table_off;
   struct PageIds {
     int32_t reg;
     const int32_t* table;
@@ -1220,10 +1244,10 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
     }
     // ---- prologue: K halves 0, 1, 2 and V(0) in flight together; S(half 0) -------------
     {
-      // table entries 0..5 (K halves 0..2), 0..3 (V tile 0)
+      // table entries 0..5 of the item (K halves 0..2), 0..3 (V tile 0): their ids are in the record
       const char* pb[6];
 #pragma unroll
-      for (int i = 0; i < 6; ++i) pb[i] = page_base(table[min(4 * t0 + i, last_pidx)]);
+      for (int i = 0; i < 6; ++i) pb[i] = page_base(item_b[2 + i]);
 #pragma unroll
       for (int i = 0; i < 6; ++i) copy_page(pb[i], false, lds_k + i * 4096);
 #pragma unroll
@@ -1377,7 +1401,7 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
         *reinterpret_cast<u32x2*>(stage + k_swz(l32, 4 * dc + j) + half * 8) = w;
       }
     if (row_ok[cb] && half == 0)
-      a.lse[(int64_t)(q0 + row0 + tt[cb]) * a.hq + hk * G + g[cb]] =
+      a.lse[(int64_t)(q_first + tt[cb]) * a.hq + hk * G + g[cb]] =
           m_run[cb] * a.scale + __logf(l_tot[cb]);
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -1391,7 +1415,7 @@ __global__ __launch_bounds__(kThreads, kCB == 1 ? 2 : 1) void attn_kernel(AttnAr
       const int rr = wave * kWaveRows + cb * 32 + lr, gg = rr % G, t2 = rr / G;
       const u32x4 v = *reinterpret_cast<const u32x4*>(stage + k_swz(lr, lane & 15));
       if (t2 < ntok)
-        *reinterpret_cast<u32x4*>(a.out + ((int64_t)(q0 + row0 + t2) * a.hq + hk * G + gg) * kRowBytes +
+        *reinterpret_cast<u32x4*>(a.out + ((int64_t)(q_first + t2) * a.hq + hk * G + gg) * kRowBytes +
                                   (lane & 15) * 16) = v;
     }
   }
@@ -1463,7 +1487,6 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
       for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
       den += sum;
       const int n = min(64, nchunks - c0);
-#pragma unroll 8
       for (int k = 0; k < n; ++k) {
         const float w = __shfl(w_lane, k);
         const f32x2 v =
