@@ -6,11 +6,13 @@
 //
 // Work
 //   * plan_kernel cuts the ragged batch into work items: a q tile (128 rows = TOK
-//     tokens x G query heads of one kv head's group, TOK = 128/G, token-major) over
-//     a range of 64-key KV tiles - the whole range, or a chunk of it when the batch
-//     alone would not fill the GPU (decode steps, short ranges over long contexts),
-//     or the prefix that neighbouring decode rows share (Sec. 3.4; fork_sequence, Sec. 3.5).
-//     Items are ordered longest first.
+//     tokens x G query heads of one kv head's group, TOK = 128/G, token-major; 256
+//     rows when the KV ranges are long) over a range of 64-key KV tiles - the whole
+//     range, or a chunk of it when the batch alone would not fill the GPU (decode
+//     steps, short ranges over long contexts), or the prefix that neighbouring
+//     sequences with short new ranges share (Sec. 3.4; fork_sequence, Sec. 3.5).
+//     Items are ordered longest first; each record holds what the kernel needs to
+//     start its first copies.
 //   * attn_kernel: one workgroup (4 wavefronts of 64) per (item, kv head), so every
 //     K/V byte staged in LDS serves the whole GQA group.  Items that cover a whole
 //     range write out/lse; the others write partial rows that merge_kernel weighs
@@ -21,7 +23,10 @@
 //   * S^T = K Q^T on v_mfma_f32_32x32x16 (A = K rows from LDS, B = Q held in
 //     registers): a lane then owns ONE query row (column l%32) and 16 keys per
 //     32-key chunk, so the softmax row max / row sum are in-lane plus one
-//     exchange with lane l^32, and the rescale factor is a per-lane scalar.
+//     exchange with lane l^32, and the rescale factor is a per-lane scalar.  With
+//     bf16 the row's reference score is fixed after the first half tile (no row max
+//     or rescale per tile; a pass whose sums left the safe range is repeated with
+//     the moving reference).
 //   * O^T += V^T P^T: P^T is the B operand straight from the S^T accumulators
 //     (no LDS round trip); V^T comes from LDS with ds_read_b64_tr_b16, which
 //     transposes 4 keys x 16 d per 16-lane group on the way in.
