@@ -218,6 +218,39 @@ __device__ int block_exclusive_scan(int v, int* lds, int* total) {
   return before + incl - v;
 }
 
+// The same for N values per thread at once (two barriers for all of them); lds holds N x 16 ints.
+template <int N>
+__device__ void block_exclusive_scan_n(int (&v)[N], int* lds, int (&total)[N]) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  int incl[N];
+#pragma unroll
+  for (int k = 0; k < N; ++k) incl[k] = v[k];
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1)
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int up = __shfl_up(incl[k], off);
+      if (lane >= off) incl[k] += up;
+    }
+  __syncthreads();               // earlier readers of lds are done
+  if (lane == 63)
+#pragma unroll
+    for (int k = 0; k < N; ++k) lds[k * (kPlanThreads / 64) + wave] = incl[k];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanThreads / 64; ++w) {
+      const int x = lds[k * (kPlanThreads / 64) + w];
+      if (w < wave) before += x;
+      all += x;
+    }
+    total[k] = all;
+    v[k] = before + incl[k] - v[k];
+  }
+}
+
 // Block-wide sum of one value per thread, to every thread: butterfly inside each wavefront, the
 // 16 wavefront sums through LDS (lds holds 2 x 16 ints).
 __device__ long long block_sum(long long v, int* lds) {
@@ -292,7 +325,7 @@ __global__ __launch_bounds__(256) void validate_pages_kernel(PlanArgs a) {
 // and orders the items by decreasing number of KV tiles (longest first), so that the tail of
 // the launch is made of short items.
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
-  __shared__ int scan[2 * kPlanThreads / 64];   // wavefront totals of the block scans and sums
+  __shared__ int scan[5 * kPlanThreads / 64];   // wavefront totals of the block scans and sums
   __shared__ int hist[kBuckets];
   __shared__ int s_err, s_maxcost;
   // per-sequence arrays of batches that fit: the searches and tile look-ups below stay in LDS
@@ -321,13 +354,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   }
   __syncthreads();
 
+  // the batch's offset arrays: from LDS when they fit there (one read of global memory in all)
+  auto cuq = [&](int i) { return cu_in_lds ? s_cuq[i] : a.cu_q[i]; };
+  auto cup = [&](int i) { return cu_in_lds ? s_cup[i] : a.cu_pages[i]; };
+  auto beg = [&](int i) { return cu_in_lds ? s_beg[i] : a.begin[i]; };
   const int per = (a.batch + kPlanThreads - 1) / kPlanThreads;
   const int s_lo = min(t * per, a.batch), s_hi = min(s_lo + per, a.batch);
   // 0. q tile width: wide tiles when a new token sees kWideMinKeys keys on average
   if (a.wide_tile_tokens > 0) {
     long long keys = 0, rows = 0;
     for (int s = s_lo; s < s_hi; ++s) {
-      const long long q = a.cu_q[s + 1] - a.cu_q[s], b = a.begin[s];
+      const long long q = cuq(s + 1) - cuq(s), b = beg(s);
       if (q > 0 && b >= 0) { rows += q; keys += q * b + q * (q + 1) / 2; }
     }
     keys = block_sum(keys, scan);
@@ -339,11 +376,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   }
   // 1. validate, count tiles per sequence (contiguous chunk of sequences per thread)
   int my_tiles = 0, err = 0, maxcost = 1;
-  if (t == 0 && (a.cu_q[0] != 0 || a.cu_q[a.batch] != a.total_q || a.cu_pages[0] < 0)) err = 1;
+  if (t == 0 && (cuq(0) != 0 || cuq(a.batch) != a.total_q || cup(0) < 0)) err = 1;
   for (int s = s_lo; s < s_hi; ++s) {
-    const int q = a.cu_q[s + 1] - a.cu_q[s], b = a.begin[s];
-    const int np = a.cu_pages[s + 1] - a.cu_pages[s];
-    if (q < 0 || b < 0 || np < 0 || a.cu_q[s] < 0 || a.cu_q[s + 1] > a.total_q) { err = 1; continue; }
+    const int q = cuq(s + 1) - cuq(s), b = beg(s);
+    const int np = cup(s + 1) - cup(s);
+    if (q < 0 || b < 0 || np < 0 || cuq(s) < 0 || cuq(s + 1) > a.total_q) { err = 1; continue; }
     if (q == 0) continue;
     const int64_t end = (int64_t)b + q + a.ahead;
     if ((end + kPage - 1) / kPage > np) { err = 1; continue; }
@@ -396,16 +433,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   int base = block_exclusive_scan(my_tiles, scan, &total_tiles);
   for (int s = s_lo; s < s_hi; ++s) {
     a.cu_tiles[s] = base;
-    const int q = a.cu_q[s + 1] - a.cu_q[s];
+    if (cu_in_lds) s_cu[s] = base;
+    const int q = cuq(s + 1) - cuq(s);
     base += (q + a.tile_tokens - 1) / a.tile_tokens;
   }
-  if (t == 0) a.cu_tiles[a.batch] = total_tiles;
+  if (t == 0) {
+    a.cu_tiles[a.batch] = total_tiles;
+    if (cu_in_lds) s_cu[a.batch] = total_tiles;
+  }
   __threadfence_block();
   __syncthreads();
-  if (cu_in_lds) {
-    for (int i = t; i <= a.batch; i += kPlanThreads) s_cu[i] = a.cu_tiles[i];
-    __syncthreads();
-  }
   if (s_err || total_tiles > a.max_tiles) {
     if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->merge_tokens = 0; a.hdr->magic = kPlanMagic; }
     return;
@@ -620,12 +657,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     for (int c = 0; c < ng; ++c)
       atomicAdd(&hist[bucket(Li > 0 ? min(Li, x.pt - c * Li) : x.pt)], 1);
   }
-  int tot_items, tot_own, tot_grp, tot_merge, tot_mtok;
-  block_exclusive_scan(n_items, scan, &tot_items);
-  int own_off = block_exclusive_scan(n_own, scan, &tot_own);
-  int grp_off = block_exclusive_scan(n_grp, scan, &tot_grp);
-  int merge_off = block_exclusive_scan(n_merge, scan, &tot_merge);
-  int mtok_off = block_exclusive_scan(n_mtok, scan, &tot_mtok);
+  int offs[5] = {n_items, n_own, n_grp, n_merge, n_mtok}, tots[5];
+  block_exclusive_scan_n(offs, scan, tots);
+  const int tot_items = tots[0], tot_own = tots[1], tot_grp = tots[2], tot_merge = tots[3],
+            tot_mtok = tots[4];
+  int own_off = offs[1], grp_off = offs[2], merge_off = offs[3], mtok_off = offs[4];
   {
     constexpr int kPer = kBuckets / kPlanThreads;
     int local[kPer], sum = 0;
