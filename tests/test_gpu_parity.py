@@ -426,6 +426,15 @@ def test_wide_q_tiles_on_long_contexts(dtype, Hq, Hkv):
     check_attention(w, sample=4096, seed=79)
 
 
+def test_wide_q_tiles_fall_back_on_overflowing_scores():
+    # scaled scores ~ N(0, 60^2) on the wide-tile kernel: rows whose later keys beat the first
+    # half tile's best by more than 2^60 send their workgroup through the moving-reference pass
+    w = small_workload(795, mi.BF16, 64, 8, [14113], [10007])
+    _scaled_kv(w, k_gain=60.0)
+    assert plan_header(w)["tile_tokens"] == 32
+    check_attention(w, sample=2048, seed=80, o_tol=peaked_o_tol(w))
+
+
 def test_short_range_over_long_context_is_cut():
     w = mi.paper_point(4500)
     h = plan_header(w)

@@ -61,6 +61,12 @@ def test_two_calls_in_a_row_the_second_smaller(dtype, Hq, Hkv):
     _check(_workload(902, dtype, Hq, Hkv, [300, 90], [299, 40]))
 
 
+def test_long_ranges_take_the_wide_tiles_through_the_array():
+    # a long new range over a long prefix: the planner picks the 256-row q tiles; no KV range is
+    # cut, so the array only holds the work list
+    _check(_workload(904, mi.BF16, 64, 8, [14113], [10007]))
+
+
 def test_a_batch_beyond_the_array_is_refused():
     w = _workload(903, mi.BF16, 8, 8, [64], [0])
     pool, db = DevPool(w), DevBatch(w)
