@@ -56,7 +56,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kBM = 128;       // rows (token x head-in-group) per workgroup
 constexpr int kBN = 64;        // keys per KV tile
 constexpr int kThreads = 256;  // 4 wavefronts, 32 rows each
-constexpr int kPlanThreads = 1024;
+constexpr int kPlanThreads = 1024;      // threads of the planner's one workgroup ...
+constexpr int kPlanThreadsSmall = 256;  // ... and for batches of few sequences and q tiles
 constexpr int kBuckets = 4096;
 constexpr int32_t kPlanMagic = 0x6d63706c;
 
@@ -194,8 +195,9 @@ struct PlanArgs {
   int32_t wide_tile_tokens, slots_wide;   // the wide q tiles, if the host allows them (else 0)
 };
 
-// Block-wide exclusive scan of one value per thread (kPlanThreads threads): a shuffle scan
+// Block-wide exclusive scan of one value per thread (NT threads): a shuffle scan
 // inside each wavefront, the 16 wavefront totals through LDS, two barriers in all.
+template <int NT>
 __device__ int block_exclusive_scan(int v, int* lds, int* total) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   int incl = v;
@@ -209,7 +211,7 @@ __device__ int block_exclusive_scan(int v, int* lds, int* total) {
   __syncthreads();
   int before = 0, all = 0;
 #pragma unroll
-  for (int w = 0; w < kPlanThreads / 64; ++w) {
+  for (int w = 0; w < NT / 64; ++w) {
     const int x = lds[w];
     if (w < wave) before += x;
     all += x;
@@ -219,7 +221,7 @@ __device__ int block_exclusive_scan(int v, int* lds, int* total) {
 }
 
 // The same for N values per thread at once (two barriers for all of them); lds holds N x 16 ints.
-template <int N>
+template <int NT, int N>
 __device__ void block_exclusive_scan_n(int (&v)[N], int* lds, int (&total)[N]) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   int incl[N];
@@ -235,14 +237,14 @@ __device__ void block_exclusive_scan_n(int (&v)[N], int* lds, int (&total)[N]) {
   __syncthreads();               // earlier readers of lds are done
   if (lane == 63)
 #pragma unroll
-    for (int k = 0; k < N; ++k) lds[k * (kPlanThreads / 64) + wave] = incl[k];
+    for (int k = 0; k < N; ++k) lds[k * (NT / 64) + wave] = incl[k];
   __syncthreads();
 #pragma unroll
   for (int k = 0; k < N; ++k) {
     int before = 0, all = 0;
 #pragma unroll
-    for (int w = 0; w < kPlanThreads / 64; ++w) {
-      const int x = lds[k * (kPlanThreads / 64) + w];
+    for (int w = 0; w < NT / 64; ++w) {
+      const int x = lds[k * (NT / 64) + w];
       if (w < wave) before += x;
       all += x;
     }
@@ -253,6 +255,7 @@ __device__ void block_exclusive_scan_n(int (&v)[N], int* lds, int (&total)[N]) {
 
 // Block-wide sum of one value per thread, to every thread: butterfly inside each wavefront, the
 // 16 wavefront sums through LDS (lds holds 2 x 16 ints).
+template <int NT>
 __device__ long long block_sum(long long v, int* lds) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
 #pragma unroll
@@ -265,12 +268,13 @@ __device__ long long block_sum(long long v, int* lds) {
   __syncthreads();
   long long all = 0;
 #pragma unroll
-  for (int w = 0; w < kPlanThreads / 64; ++w)
+  for (int w = 0; w < NT / 64; ++w)
     all += ((long long)lds[2 * w + 1] << 32) | (unsigned int)lds[2 * w];
   return all;
 }
 
 // Block-wide inclusive running maximum of one value per thread.
+template <int NT>
 __device__ int block_inclusive_max_scan(int v, int* lds) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   int incl = v;
@@ -284,7 +288,7 @@ __device__ int block_inclusive_max_scan(int v, int* lds) {
   __syncthreads();
   int before = INT32_MIN;
 #pragma unroll
-  for (int w = 0; w < kPlanThreads / 64; ++w)
+  for (int w = 0; w < NT / 64; ++w)
     if (w < wave) before = max(before, lds[w]);
   return max(before, incl);
 }
@@ -324,8 +328,11 @@ __global__ __launch_bounds__(256) void validate_pages_kernel(PlanArgs a) {
 // have too few work items to fill the GPU (decode rows, short batches over long contexts),
 // and orders the items by decreasing number of KV tiles (longest first), so that the tail of
 // the launch is made of short items.
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
-  __shared__ int scan[5 * kPlanThreads / 64];   // wavefront totals of the block scans and sums
+// NT threads: 1024, or 256 for small batches, whose many block-wide steps then cost a quarter
+// of the wavefronts to synchronise.
+template <int NT>
+__global__ __launch_bounds__(NT) void plan_kernel(PlanArgs a) {
+  __shared__ int scan[5 * NT / 64];   // wavefront totals of the block scans and sums
   __shared__ int hist[kBuckets];
   __shared__ int s_err, s_maxcost;
   // per-sequence arrays of batches that fit: the searches and tile look-ups below stay in LDS
@@ -333,9 +340,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       s_cup[kCuTilesInLds + 1];
   // shared-prefix groups, per sequence: pages in common with the next sequence; prefix tiles the
   // group covers (0 = not in a group); the group's first sequence (-1 = none); at that first
-  // sequence the group's size and the base of its partial rows
+  // sequence the group's new tokens, the base of its partial rows and its last sequence
   __shared__ int s_common[kCuTilesInLds], s_gp[kCuTilesInLds], s_glead[kCuTilesInLds],
-      s_gsize[kCuTilesInLds], s_gbase[kCuTilesInLds];
+      s_gsize[kCuTilesInLds], s_gbase[kCuTilesInLds], s_glast[kCuTilesInLds];
   __shared__ int s_groups;
   // remainder round: flags of the q tiles that are cut, the cost bucket at the boundary and how
   // many tiles of it are taken
@@ -343,10 +350,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   __shared__ int s_tail_bucket, s_tail_take, s_tail_taken;
   const int t = threadIdx.x;
   if (t == 0) { s_err = 0; s_maxcost = 1; }
-  for (int i = t; i < kBuckets; i += kPlanThreads) hist[i] = 0;
+  for (int i = t; i < kBuckets; i += NT) hist[i] = 0;
   const bool cu_in_lds = a.batch <= kCuTilesInLds;
   if (cu_in_lds) {
-    for (int i = t; i <= a.batch; i += kPlanThreads) {
+    for (int i = t; i <= a.batch; i += NT) {
       s_cuq[i] = a.cu_q[i];
       s_cup[i] = a.cu_pages[i];
       if (i < a.batch) s_beg[i] = a.begin[i];
@@ -358,7 +365,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   auto cuq = [&](int i) { return cu_in_lds ? s_cuq[i] : a.cu_q[i]; };
   auto cup = [&](int i) { return cu_in_lds ? s_cup[i] : a.cu_pages[i]; };
   auto beg = [&](int i) { return cu_in_lds ? s_beg[i] : a.begin[i]; };
-  const int per = (a.batch + kPlanThreads - 1) / kPlanThreads;
+  const int per = (a.batch + NT - 1) / NT;
   const int s_lo = min(t * per, a.batch), s_hi = min(s_lo + per, a.batch);
   // 0. q tile width: wide tiles when a new token sees kWideMinKeys keys on average
   if (a.wide_tile_tokens > 0) {
@@ -367,8 +374,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       const long long q = cuq(s + 1) - cuq(s), b = beg(s);
       if (q > 0 && b >= 0) { rows += q; keys += q * b + q * (q + 1) / 2; }
     }
-    keys = block_sum(keys, scan);
-    rows = block_sum(rows, scan);
+    keys = block_sum<NT>(keys, scan);
+    rows = block_sum<NT>(rows, scan);
     if (rows > 0 && keys / rows >= kWideMinKeys) {
       a.tile_tokens = a.wide_tile_tokens;
       a.slots = a.slots_wide;
@@ -387,8 +394,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     my_tiles += (q + a.tile_tokens - 1) / a.tile_tokens;
     maxcost = max(maxcost, (int)((end + kBN - 1) / kBN));
   }
-  if (err) atomicOr(&s_err, 1);
-  atomicMax(&s_maxcost, maxcost);
+  // (one LDS atomic per wavefront, not per thread: 1024 atomics on one address take microseconds)
+  if (__ballot(err != 0) != 0 && (t & 63) == 0) atomicOr(&s_err, 1);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) maxcost = max(maxcost, __shfl_xor(maxcost, off));
+  if ((t & 63) == 0) atomicMax(&s_maxcost, maxcost);
   __syncthreads();
   if (s_err) {
     if (t == 0) { a.hdr->err = MC_ERR_RANGE; a.hdr->num_items = 0; a.hdr->num_merges = 0; a.hdr->merge_tokens = 0; a.hdr->magic = kPlanMagic; }
@@ -399,7 +409,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   //    bound by memory latency); entries beyond the first 512 of a sequence follow one
   //    sequence at a time.
   if (a.batch <= kValidateInPlan) {
-    for (int s4 = (t >> 6) * 4; s4 < a.batch; s4 += (kPlanThreads >> 6) * 4) {
+    for (int s4 = (t >> 6) * 4; s4 < a.batch; s4 += (NT >> 6) * 4) {
       int32_t pg[4][8];
       int need[4], p0[4];
 #pragma unroll
@@ -427,10 +437,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     }
   }
   // (batches beyond that: validate_pages_kernel, launched after this kernel, on many workgroups)
-  if (err) atomicOr(&s_err, 1);
+  if (__ballot(err != 0) != 0 && (t & 63) == 0) atomicOr(&s_err, 1);
   // 3. exclusive scan of tiles per sequence
   int total_tiles;
-  int base = block_exclusive_scan(my_tiles, scan, &total_tiles);
+  int base = block_exclusive_scan<NT>(my_tiles, scan, &total_tiles);
   for (int s = s_lo; s < s_hi; ++s) {
     a.cu_tiles[s] = base;
     if (cu_in_lds) s_cu[s] = base;
@@ -454,10 +464,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   //     as one q tile - their tokens are neighbours in the q array, and every key of the prefix
   //     lies before every one of them, so no mask is involved - one K/V read for all of them,
   //     and their own remainders one by one; the parts are merged by LSE like any other chunks.
-  const bool try_groups = a.allow_groups && cu_in_lds && a.batch >= 2;
+  const bool try_groups = a.allow_groups && cu_in_lds && a.batch >= 2 && a.batch <= NT;
   if (t == 0) s_groups = 0;
   if (try_groups) {
-    for (int i = t; i < a.batch; i += kPlanThreads) { s_common[i] = 0; s_gp[i] = 0; s_glead[i] = -1; s_gsize[i] = 0; }
+    for (int i = t; i < a.batch; i += NT) { s_common[i] = 0; s_gp[i] = 0; s_glead[i] = -1; s_gsize[i] = 0; }
     __syncthreads();
     // pages in common between s and s+1, among the whole pages cached by both.  First every
     // pair at once, one thread each: unrelated sequences differ in their first page and are
@@ -473,7 +483,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         a.page_table[s_cup[t]] == a.page_table[s_cup[t + 1]])
       s_common[t] = 1;
     __syncthreads();
-    for (int sq = t >> 6; sq + 1 < a.batch; sq += kPlanThreads >> 6) {
+    for (int sq = t >> 6; sq + 1 < a.batch; sq += NT >> 6) {
       if (s_common[sq] == 0) continue;
       const int lim = min(s_beg[sq], s_beg[sq + 1]) / kPage;
       const int pa = s_cup[sq], pb = s_cup[sq + 1];
@@ -488,44 +498,64 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       if ((t & 63) == 0) s_common[sq] = common;
     }
     __syncthreads();
-    // runs of such sequences linked by enough common pages, cut into groups of at most
-    // tile_tokens new tokens: the thread of a run's first sequence walks the run
+    // Runs of such sequences linked by enough common pages, cut greedily into groups of at most
+    // tile_tokens new tokens.  The thread of a run's first sequence walks the run group by
+    // group (cu_q is the prefix sum of the new tokens: the end of a group is a binary search);
+    // everything per member is done by the member's own thread.
     const bool mine = t < a.batch;
     auto linked = [&](int sq) {   // sq and sq+1 sit in one run
       return sq >= 0 && sq + 1 < a.batch && is_short(sq) && is_short(sq + 1) &&
              s_common[sq] >= kMinPages;
     };
-    if (mine && is_short(t) && !linked(t - 1) && linked(t)) {
-      int lead = t, tokens = 0, members = 0, pages = INT32_MAX;
-      auto close_group = [&]() {
-        if (members >= 2) {
-          s_gsize[lead] = tokens;                          // rows of the group's q tile
-          s_gbase[lead] = (pages / (2 * kBN / kPage)) * 2; // prefix tiles, even (scratch until step 5)
-          s_groups = 1;
-        } else {
-          s_glead[lead] = -1;
-        }
-      };
-      for (int sq = t;; ++sq) {
-        const int q = s_cuq[sq + 1] - s_cuq[sq];
-        if (tokens + q > a.tile_tokens) {                  // the tile is full: next group
-          close_group();
-          lead = sq; tokens = 0; members = 0; pages = INT32_MAX;
-        }
-        if (members > 0) pages = min(pages, s_common[sq - 1]);
-        s_glead[sq] = lead;
-        tokens += q;
-        ++members;
-        if (!linked(sq)) break;
-      }
-      close_group();
-    }
+    const bool in_run = mine && is_short(t) && (linked(t) || linked(t - 1));
+    // (unrelated sequences, the usual case: nothing is linked and the rest is skipped)
+    if (__ballot(in_run) != 0 && (t & 63) == 0) s_groups = -1;
     __syncthreads();
-    // every member learns the prefix its group covers (a lead without a group has none)
-    if (mine) {
-      const int lead = s_glead[t];
-      if (lead >= 0 && s_gsize[lead] > 0) s_gp[t] = s_gbase[lead];
-      else s_glead[t] = -1;
+    const bool any_run = s_groups != 0;
+    __syncthreads();
+    if (t == 0) s_groups = 0;
+    if (any_run) {
+      // last sequence of the run a sequence sits in: the nearest j >= t that is not linked to j + 1
+      // (a running maximum over the reversed index)
+      {
+        const int j = a.batch - 1 - t;     // this thread's element of the reversed scan
+        const bool ends = j >= 0 && !linked(j);
+        const int v = block_inclusive_max_scan<NT>(ends ? -j : INT32_MIN, scan);
+        if (j >= 0) s_gbase[j] = -v;       // scratch until step 5: run end of sequence j
+      }
+      __syncthreads();
+      if (in_run && !linked(t - 1)) {      // first sequence of a run
+        const int run_end = s_gbase[t];
+        for (int lead = t; lead <= run_end;) {
+          // the last member: the largest e <= run_end with cu_q[e + 1] - cu_q[lead] <= tile_tokens
+          int lo = lead, hi = run_end;
+          const int limit = s_cuq[lead] + a.tile_tokens;
+          while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_cuq[mid + 1] <= limit) lo = mid; else hi = mid - 1;
+          }
+          if (lo > lead) {                 // two members or more: a group
+            s_gsize[lead] = s_cuq[lo + 1] - s_cuq[lead];   // rows of the group's q tile
+            s_glast[lead] = lo;
+            s_gbase[lead] = INT32_MAX;     // becomes the fewest pages two neighbouring members share
+            s_groups = 1;
+          }
+          lead = lo + 1;
+        }
+      }
+      __syncthreads();
+      // every sequence finds the nearest group lead at or before it and checks that it is a member
+      const int near = block_inclusive_max_scan<NT>(mine && s_gsize[t] > 0 ? t : -1, scan);
+      const bool member = in_run && near >= 0 && t <= s_glast[near];
+      if (member && t < s_glast[near]) atomicMin(&s_gbase[near], s_common[t]);
+      __syncthreads();
+      if (member && t == near)
+        s_gbase[t] = (s_gbase[t] / (2 * kBN / kPage)) * 2;   // prefix tiles, even (scratch until step 5)
+      __syncthreads();
+      if (mine) {
+        s_glead[t] = member ? near : -1;
+        s_gp[t] = member ? s_gbase[near] : 0;
+      }
     }
     __syncthreads();
   }
@@ -563,8 +593,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   };
   auto total_part_rows = [&](int L) {   // block-wide
     long long rows = 0;
-    for (int i = t; i < total_tiles; i += kPlanThreads) rows += part_rows(locate(i), L);
-    return block_sum(rows, scan);
+    for (int i = t; i < total_tiles; i += NT) rows += part_rows(locate(i), L);
+    return block_sum<NT>(rows, scan);
   };
 
   // 4. chunk length.  No cutting when the q tiles alone give the GPU kRoundsWanted rounds of
@@ -573,11 +603,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   int L = 0;
   if ((int64_t)total_tiles * a.hkv < (int64_t)kRoundsWanted * a.slots) {
     long long cost = 0;
-    for (int i = t; i < total_tiles; i += kPlanThreads) {
+    for (int i = t; i < total_tiles; i += NT) {
       const Tile x = locate(i);
       cost += x.T - x.pt + (x.gm ? x.pt : 0);
     }
-    cost = block_sum(cost, scan);
+    cost = block_sum<NT>(cost, scan);
     const long long want =
         (cost * a.hkv + (long long)kItemsPerSlot * a.slots - 1) / ((long long)kItemsPerSlot * a.slots);
     L = want < kMinChunkTiles ? kMinChunkTiles : want > (1 << 28) ? (1 << 28) : (int)want;
@@ -609,13 +639,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         n < (int64_t)kRoundsWanted * a.slots && rem_tiles >= 1 && 10 * rem <= 7 * a.slots && c >= 2 &&
         (int64_t)rem_tiles * a.tile_tokens * c <= a.part_cap) {
       if (t == 0) { s_tail_bucket = kBuckets; s_tail_take = 0; s_tail_taken = 0; }
-      for (int i = t; i < total_tiles; i += kPlanThreads) atomicAdd(&hist[bucket(locate(i).T)], 1);
+      for (int i = t; i < total_tiles; i += NT) atomicAdd(&hist[bucket(locate(i).T)], 1);
       __syncthreads();
       // shortest first: walk the buckets from the last to the first until rem_tiles tiles are in
-      constexpr int kPer = kBuckets / kPlanThreads;
+      constexpr int kPer = kBuckets / NT;
       int local[kPer], sum = 0;
       for (int i = 0; i < kPer; ++i) { local[i] = hist[kBuckets - 1 - (t * kPer + i)]; sum += local[i]; }
-      int tot, before = block_exclusive_scan(sum, scan, &tot);
+      int tot, before = block_exclusive_scan<NT>(sum, scan, &tot);
       for (int i = 0; i < kPer; ++i) {
         if (before < rem_tiles && before + local[i] >= rem_tiles) {
           s_tail_bucket = kBuckets - 1 - (t * kPer + i);
@@ -624,12 +654,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         before += local[i];
       }
       __syncthreads();
-      for (int i = t; i < total_tiles; i += kPlanThreads) {
+      for (int i = t; i < total_tiles; i += NT) {
         const int bk = bucket(locate(i).T);
         s_tailflag[i] = bk > s_tail_bucket ||
                         (bk == s_tail_bucket && atomicAdd(&s_tail_taken, 1) < s_tail_take);
       }
-      for (int i = t; i < kBuckets; i += kPlanThreads) hist[i] = 0;
+      for (int i = t; i < kBuckets; i += NT) hist[i] = 0;
       __syncthreads();
       tail_c = c;
     }
@@ -642,7 +672,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
   };
 
   // 5. items and merge records: count per contiguous range of tiles, scan, histogram of costs
-  const int tper = (total_tiles + kPlanThreads - 1) / kPlanThreads;
+  const int tper = (total_tiles + NT - 1) / NT;
   const int i_lo = min(t * tper, total_tiles), i_hi = min(i_lo + tper, total_tiles);
   int n_items = 0, n_own = 0, n_grp = 0, n_merge = 0, n_mtok = 0;
   for (int i = i_lo; i < i_hi; ++i) {
@@ -658,15 +688,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
       atomicAdd(&hist[bucket(Li > 0 ? min(Li, x.pt - c * Li) : x.pt)], 1);
   }
   int offs[5] = {n_items, n_own, n_grp, n_merge, n_mtok}, tots[5];
-  block_exclusive_scan_n(offs, scan, tots);
+  block_exclusive_scan_n<NT>(offs, scan, tots);
   const int tot_items = tots[0], tot_own = tots[1], tot_grp = tots[2], tot_merge = tots[3],
             tot_mtok = tots[4];
   int own_off = offs[1], grp_off = offs[2], merge_off = offs[3], mtok_off = offs[4];
   {
-    constexpr int kPer = kBuckets / kPlanThreads;
+    constexpr int kPer = kBuckets / NT;
     int local[kPer], sum = 0;
     for (int i = 0; i < kPer; ++i) { local[i] = hist[t * kPer + i]; sum += local[i]; }
-    int tot, off = block_exclusive_scan(sum, scan, &tot);
+    int tot, off = block_exclusive_scan<NT>(sum, scan, &tot);
     for (int i = 0; i < kPer; ++i) { hist[t * kPer + i] = off; off += local[i]; }
   }
   __syncthreads();
@@ -1660,8 +1690,14 @@ mc_status plan_impl(const mc_pool_desc* pool, int32_t num_q_heads, int32_t batch
   a.max_items = item_bound(w, a.hkv, a.slots, a.allow_groups);
   a.part_cap = w.part_cap;
   a.ahead = ahead_tokens;
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0,
-                     static_cast<hipStream_t>(stream), a);
+  // (few sequences only: the page-id checks and the table comparisons of shared prefixes go
+  // a wavefront per sequence or pair and want the wavefronts of the large workgroup)
+  if (batch <= 16 && w.max_tiles <= 8 * kPlanThreadsSmall)
+    hipLaunchKernelGGL(plan_kernel<kPlanThreadsSmall>, dim3(1), dim3(kPlanThreadsSmall), 0,
+                       static_cast<hipStream_t>(stream), a);
+  else
+    hipLaunchKernelGGL(plan_kernel<kPlanThreads>, dim3(1), dim3(kPlanThreads), 0,
+                       static_cast<hipStream_t>(stream), a);
   if (batch > kValidateInPlan)
     hipLaunchKernelGGL(validate_pages_kernel, dim3((batch + 3) / 4), dim3(256), 0,
                        static_cast<hipStream_t>(stream), a);
