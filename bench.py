@@ -32,7 +32,7 @@ ATTN_WORKLOADS = ["cfg2", "cfg3-passB", "cfg4", "cfg5-16k", "cfg5-32k", "paper-5
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this very
 # command with the default seed (counters scaled by what a plain 4 GiB copy reads; see
 # profiles/bench_cfg2_hbm_traffic.md).  Valid only for the default workload.
-MEASURED_TRAFFIC = {"seed": 2000, "attention_bytes": int((360.6 + 79.8) * 2**20),
+MEASURED_TRAFFIC = {"seed": 2000, "attention_bytes": int((380.2 + 79.8) * 2**20),
                     "pack_4GiB_bytes": int((4096.2 + 4096.1) * 2**20)}
 
 
