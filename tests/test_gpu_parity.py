@@ -413,13 +413,15 @@ def test_large_batch_is_not_cut():
     assert h["chunk_tiles"] == 0 and h["num_merges"] == 0 and h["num_items"] >= 300, h
 
 
-@pytest.mark.parametrize("dtype,Hq,Hkv", [(mi.BF16, 32, 8), (mi.F16, 32, 8), (mi.BF16, 64, 8)])
+@pytest.mark.parametrize("dtype,Hq,Hkv", [(mi.BF16, 32, 8), (mi.F16, 32, 8), (mi.BF16, 64, 8),
+                                          (mi.BF16, 16, 8), (mi.F16, 8, 8)])
 def test_wide_q_tiles_on_long_contexts(dtype, Hq, Hkv):
     """Long new ranges over long cached prefixes: the planner takes q tiles of 256 rows (the
     kernel variant with two row blocks per wavefront).  Unaligned begins and lengths, a ragged
     last tile; a sample spread over both sequences against the oracle."""
     G = Hq // Hkv
-    lens, begins = ([17013, 13107], [12001, 9007]) if G == 4 else ([14113], [10007])
+    lens, begins = {1: ([42013], [9005]), 2: ([26511], [10003]), 4: ([17013, 13107], [12001, 9007]),
+                    8: ([14113], [10007])}[G]
     w = small_workload(790 + Hq + dtype, dtype, Hq, Hkv, lens, begins)
     h = plan_header(w)
     assert h["tile_tokens"] == 256 // G and h["num_merges"] == 0, h
